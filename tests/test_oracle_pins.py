@@ -1,0 +1,287 @@
+"""Pins for the CPU oracle: everything here checks oracle/ against something other
+than itself -- hand-worked fixtures, closed forms, invariants, independent NumPy
+formulations, exact integer arithmetic and brute force.  CPU only."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from oracle import q8_oracle as O
+from paper_1910_06188_amd import synth
+
+
+def _load(golden_dir, name):
+    with open(os.path.join(golden_dir, name)) as f:
+        return json.load(f)
+
+
+# ---------------------------------------------------------------- Eq. 1-3, hand cases
+def test_quantize_hand_cases(golden_dir):
+    for c in _load(golden_dir, "quantize_cases.json")["cases"]:
+        x = np.array(c["x"], dtype=np.float32)
+        if c["dynamic"]:
+            a = O.absmax(x)
+            assert a == np.float32(c["amax"]), c["name"]
+            s = O.scale(a)
+            assert s == np.float32(c["scale"]), c["name"]
+        else:
+            s = np.float32(c["scale"])
+        q = O.quantize(x, s)
+        assert q.dtype == np.int8
+        assert q.tolist() == c["q"], c["name"]
+
+
+def test_bias_hand_cases(golden_dir):
+    for c in _load(golden_dir, "bias_cases.json")["cases"]:
+        b = np.array(c["b"], dtype=np.float32)
+        bq = O.quantize_bias(b, b.size, c["sx"], c["sw"])
+        assert bq.dtype == np.int32
+        assert bq.tolist() == c["bq"], c["name"]
+    assert O.quantize_bias(None, 4, 3.0, [5.0]).tolist() == [0, 0, 0, 0]
+
+
+def test_dequant_hand_cases(golden_dir):
+    for c in _load(golden_dir, "dequant_cases.json")["cases"]:
+        acc = np.array(c["acc"], dtype=np.int32)
+        y = O.dequant(acc, c["sx"], c["sw"])
+        assert y.dtype == np.float32
+        np.testing.assert_array_equal(y, np.array(c["y"], dtype=np.float64).astype(np.float32), c["name"])
+
+
+def test_gelu_tabulated_values(golden_dir):
+    g = _load(golden_dir, "gelu_values.json")
+    out = O.gelu(np.array(g["v"], dtype=np.float32)).astype(np.float64)
+    np.testing.assert_allclose(out, np.array(g["gelu"]), rtol=2e-7, atol=0)
+
+
+def test_gelu_against_library_cdf_and_identity():
+    from scipy.special import ndtr  # a different routine from the oracle's erfc
+    v = np.linspace(-9, 9, 20001).astype(np.float32)
+    out = O.gelu(v).astype(np.float64)
+    np.testing.assert_allclose(out, v.astype(np.float64) * ndtr(v.astype(np.float64)), rtol=2e-7, atol=1e-300)
+    # v*Phi(v) - (-v)*Phi(-v) = v
+    np.testing.assert_allclose(out - O.gelu(-v).astype(np.float64), v.astype(np.float64), rtol=3e-7, atol=1e-7)
+
+
+# ---------------------------------------------------------------- invariants of Eq. 1
+def test_quantize_invariants():
+    g = synth.rng(11)
+    x = (g.standard_normal(200_000, dtype=np.float32) * np.float32(3.0)).astype(np.float32)
+    a = O.absmax(x)
+    assert a == np.abs(x).max()
+    assert O.absmax(g.permutation(x)) == a          # permutation invariant
+    s = O.scale(a)
+    assert s == np.float32(127.0) / a               # one binary32 division
+    q = O.quantize(x, s).astype(np.int32)
+    assert q.min() >= -127 and q.max() <= 127       # -128 never produced
+    assert abs(q[np.argmax(np.abs(x))]) == 127      # the extreme maps to +-M
+    assert np.all((q == 0) | (np.sign(q) == np.sign(x)))
+    order = np.argsort(x, kind="stable")
+    assert np.all(np.diff(q[order]) >= 0)           # monotone
+    np.testing.assert_array_equal(O.quantize(-x, s).astype(np.int32), -q)  # odd symmetry
+    # rounding error at most half a step wherever no clamping happens
+    assert np.max(np.abs(x.astype(np.float64) * np.float64(s) - q)) <= 0.5 + 1e-4
+
+
+def test_quantize_matches_independent_float64_formulation():
+    """p is a binary32 value, so |p| + 0.5 is exact in binary64: floor(|p|+0.5) with the
+    sign restored is round-half-away with no double rounding."""
+    g = synth.rng(12)
+    for s in (np.float32(1.0), np.float32(24.413), np.float32(1270.5), np.float32(0.037)):
+        x = (g.standard_normal(300_000, dtype=np.float32) * np.float32(4.0 / float(s) * 30)).astype(np.float32)
+        # add exact ties and near-ties
+        ties = (np.arange(-130, 131, dtype=np.float32) + np.float32(0.5)) / s
+        x = np.concatenate([x, ties, np.nextafter(ties, np.float32(np.inf)), np.nextafter(ties, np.float32(-np.inf))])
+        p = x.astype(np.float32) * np.float32(s)
+        assert p.dtype == np.float32
+        p64 = p.astype(np.float64)
+        ref = np.clip(np.sign(p64) * np.floor(np.abs(p64) + 0.5), -127, 127).astype(np.int8)
+        np.testing.assert_array_equal(O.quantize(x, s), ref)
+
+
+def test_quantize_exhaustive_near_half_integers():
+    """Every float within a few ulps of every half-integer in range, scale 1."""
+    base = np.arange(-128, 129, dtype=np.float32)[:, None] + np.float32(0.5)
+    x = base
+    cols = [base]
+    up, dn = base, base
+    for _ in range(4):
+        up = np.nextafter(up, np.float32(np.inf))
+        dn = np.nextafter(dn, np.float32(-np.inf))
+        cols += [up, dn]
+    x = np.concatenate(cols, axis=1).reshape(-1).astype(np.float32)
+    q = O.quantize(x, 1.0).astype(np.int64)
+    # python-level definition with exact rationals
+    from fractions import Fraction
+    exp = []
+    for v in x.tolist():
+        f = Fraction(v)
+        n = int(abs(f) + Fraction(1, 2))  # floor(|v| + 1/2): half goes away from zero
+        n = -n if f < 0 else n
+        exp.append(max(-127, min(127, n)))
+    assert q.tolist() == exp
+
+
+def test_bias_matches_independent_formulation():
+    g = synth.rng(13)
+    b = synth.bias(g, 4096)
+    sx, sw = np.float32(24.4), np.float32(1234.5)
+    sb = np.float32(sx * sw)
+    p = (b * sb).astype(np.float32).astype(np.float64)
+    ref = (np.sign(p) * np.floor(np.abs(p) + 0.5)).astype(np.int64)
+    np.testing.assert_array_equal(O.quantize_bias(b, b.size, sx, sw).astype(np.int64), ref)
+
+
+def test_nonfinite_and_shape_errors():
+    with pytest.raises(O.OracleError):
+        O.absmax(np.array([1.0, np.nan], dtype=np.float32))
+    with pytest.raises(O.OracleError):
+        O.quantize(np.array([np.inf], dtype=np.float32), 1.0)
+    with pytest.raises(O.OracleError):
+        O.scale(np.float32(1e-45))  # 127/denormal overflows: outside the method's domain
+    with pytest.raises(O.OracleError):
+        O.quantize_bias(np.zeros(5, np.float32), 5, 1.0, [1.0, 2.0])  # 5 columns, 2 groups
+
+
+# ---------------------------------------------------------------- integer GEMM
+def test_gemm_bruteforce_tiny_python_ints():
+    g = synth.rng(14)
+    for _ in range(40):
+        M, N, K = (int(v) for v in g.integers(1, 5, size=3))
+        xq = synth.random_int8(g, (M, K))
+        wq = synth.random_int8(g, (N, K))
+        bq = g.integers(-1000, 1000, size=N).astype(np.int32)
+        acc = O.gemm_i8(xq, wq, bq)
+        for m in range(M):
+            for n in range(N):
+                s = int(bq[n]) + sum(int(xq[m, k]) * int(wq[n, k]) for k in range(K))
+                assert int(acc[m, n]) == s
+    # asymmetric operands: a transposed or swapped operand cannot pass
+    xq = np.array([[1, 2, 3], [4, 5, 6]], dtype=np.int8)          # [2,3]
+    wq = np.array([[1, 0, 0], [0, 1, 0], [0, 0, 1], [1, 1, 1]], dtype=np.int8)  # [4,3]
+    assert O.gemm_i8(xq, wq).tolist() == [[1, 2, 3, 6], [4, 5, 6, 15]]
+
+
+def test_gemm_all_int8_pairs():
+    v = np.arange(-128, 128, dtype=np.int64)
+    xq = v.astype(np.int8).reshape(-1, 1)
+    wq = v.astype(np.int8).reshape(-1, 1)
+    acc = O.gemm_i8(xq, wq)
+    np.testing.assert_array_equal(acc.astype(np.int64), np.outer(v, v))
+
+
+@pytest.mark.parametrize("M,N,K,seed", [(16, 768, 768, 0), (96, 3072, 768, 1), (64, 768, 3072, 2), (40, 1024, 4096, 3)])
+def test_gemm_matches_exact_blas_on_integers(M, N, K, seed):
+    """float64 matmul of small integers is exact (|sum| < 2^53), and it is a different
+    routine from the oracle's triple loop."""
+    g = synth.rng(seed)
+    xq = synth.random_int8(g, (M, K))
+    wq = synth.random_int8(g, (N, K))
+    bq = g.integers(-5000, 5000, size=N).astype(np.int32)
+    ref = (xq.astype(np.float64) @ wq.T.astype(np.float64)).astype(np.int64) + bq.astype(np.int64)
+    np.testing.assert_array_equal(O.gemm_i8(xq, wq, bq, threads=4).astype(np.int64), ref)
+    np.testing.assert_array_equal(O.gemm_i8(xq, wq, bq, threads=1).astype(np.int64), ref)
+
+
+def test_gemm_int32_exactness_stress():
+    K = 4095
+    xq = np.full((3, K), 127, dtype=np.int8)
+    wq = np.full((2, K), -127, dtype=np.int8)
+    assert np.all(O.gemm_i8(xq, wq) == -66_048_255)      # odd and > 2^24: no fp32 accumulation survives
+    alt = np.where(np.arange(K) % 2 == 0, 127, -127).astype(np.int8)
+    assert int(O.gemm_i8(alt[None, :], np.full((1, K), 127, np.int8))[0, 0]) == 16129  # K odd: one term left
+    # int32 range boundary: 127*127*K <= 2^31-1 exactly when K <= 133144
+    big = 133_144
+    assert int(O.gemm_i8(np.full((1, big), 127, np.int8), np.full((1, big), 127, np.int8))[0, 0]) == 16129 * big
+    with pytest.raises(O.OracleError):
+        O.gemm_i8(np.full((1, big + 1), 127, np.int8), np.full((1, big + 1), 127, np.int8))
+
+
+# ---------------------------------------------------------------- whole layer
+def test_linear_closed_form_constant_tensors():
+    """x == c > 0 and W == w > 0, no bias: every code is 127, acc = 127^2 K, y = K c w."""
+    M, N, K = 5, 7, 96
+    c, w = np.float32(0.75), np.float32(0.031)
+    x = np.full((M, K), c, dtype=np.float32)
+    W = np.full((N, K), w, dtype=np.float32)
+    wq, sw = O.quantize_tensor(W)
+    r = O.linear(x, wq, sw)
+    assert np.all(r["xq"] == 127) and np.all(wq == 127)
+    assert np.all(r["acc"] == 16129 * K)
+    np.testing.assert_allclose(r["y"], K * float(c) * float(w), rtol=1e-6)
+
+
+def test_linear_zero_input_gives_bias():
+    M, N, K = 3, 8, 32
+    g = synth.rng(15)
+    W = synth.weights(g, N, K)
+    b = synth.bias(g, N)
+    wq, sw = O.quantize_tensor(W)
+    r = O.linear(np.zeros((M, K), np.float32), wq, sw, b)
+    assert r["sx"] == 1.0 and not r["xq"].any()
+    np.testing.assert_array_equal(r["acc"], np.broadcast_to(r["bq"], (M, N)))
+    np.testing.assert_allclose(r["y"], np.broadcast_to(b, (M, N)), atol=0.5 / float(sw) + 1e-9)
+
+
+@pytest.mark.parametrize("M,K,N,seed", [(16, 768, 768, 0), (64, 768, 3072, 21), (32, 3072, 768, 22)])
+def test_linear_error_bound_vs_dense_product(M, K, N, seed):
+    """Eq. 1 rounds each operand by at most half a step, so against the exact fp64
+    product |y - ref| <= sum_k(|x_k|/(2 S_W) + |w_k|/(2 S_x) + 1/(4 S_x S_W)) + 1/(2 S_x S_W)."""
+    d = synth.fc_layer(seed, M, K, N)
+    x, W, b = d["x"], d["W"], d["b"]
+    wq, sw = O.quantize_tensor(W)
+    r = O.linear(x, wq, sw, b)
+    sx = float(r["sx"])
+    sw = float(sw)
+    ref = x.astype(np.float64) @ W.T.astype(np.float64) + b.astype(np.float64)
+    bound = (np.abs(x).astype(np.float64).sum(1)[:, None] / (2 * sw)
+             + np.abs(W).astype(np.float64).sum(1)[None, :] / (2 * sx)
+             + K / (4 * sx * sw) + 1 / (2 * sx * sw))
+    err = np.abs(r["y"].astype(np.float64) - ref)
+    assert np.all(err <= bound * (1 + 1e-5) + 1e-6)
+    # and the approximation is actually good, not vacuously bounded
+    assert np.sqrt(np.mean(err ** 2)) < 0.02 * np.sqrt(np.mean(ref ** 2))
+
+
+def test_linear_grouped_scales_equal_three_separate_layers():
+    """A fused Q|K|V projection with one S_W per group is bit-identical to three layers."""
+    g = synth.rng(16)
+    M, K, H = 24, 64, 48
+    x = synth.activations(g, M, K)
+    Ws = [synth.weights(g, H, K) * np.float32(f) for f in (1.0, 2.5, 0.3)]
+    bs = [synth.bias(g, H) for _ in range(3)]
+    qs = [O.quantize_tensor(W) for W in Ws]
+    fused = O.linear(x, np.concatenate([q for q, _ in qs]), [s for _, s in qs], np.concatenate(bs))
+    for i, ((wq, sw), b) in enumerate(zip(qs, bs)):
+        r = O.linear(x, wq, sw, b)
+        np.testing.assert_array_equal(fused["acc"][:, i * H:(i + 1) * H], r["acc"])
+        np.testing.assert_array_equal(fused["y"][:, i * H:(i + 1) * H], r["y"])
+
+
+# ---------------------------------------------------------------- embedding
+def test_embedding_is_a_row_copy_and_dequant():
+    g = synth.rng(17)
+    V, H = 1000, 48
+    E = synth.weights(g, V, H)
+    eq, se = O.quantize_tensor(E)
+    ids = np.array([0, V - 1, 5, 5, 999, 0, 123], dtype=np.int32)
+    out_i8, out_f = O.embedding(eq, se, ids)
+    for t, i in enumerate(ids):
+        assert out_i8[t].tobytes() == eq[i].tobytes()
+    np.testing.assert_allclose(out_f, eq[ids].astype(np.float64) / float(se), rtol=1e-7)
+    np.testing.assert_allclose(out_f, E[ids], atol=0.5 / float(se) * 1.0001)
+    for bad in (V, -1):
+        with pytest.raises(O.OracleError):
+            O.embedding(eq, se, np.array([1, bad], dtype=np.int32))
+
+
+def test_embedding_sum3_matches_fp64_sum():
+    g = synth.rng(18)
+    H = 32
+    tabs = [synth.weights(g, v, H) for v in (200, 64, 2)]
+    qs = [O.quantize_tensor(t) for t in tabs]
+    ids = [g.integers(0, v, size=50, dtype=np.int32) for v in (200, 64, 2)]
+    out = O.embedding_sum3(qs[0][0], qs[0][1], qs[1][0], qs[1][1], qs[2][0], qs[2][1], *ids)
+    ref = sum(q[i].astype(np.float64) / float(s) for (q, s), i in zip(qs, ids))
+    np.testing.assert_allclose(out, ref, rtol=1e-6, atol=1e-9)
