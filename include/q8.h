@@ -1,0 +1,149 @@
+/*
+ * q8 -- symmetric linear int8 quantized fully-connected layer and int8 embedding
+ * lookup for AMD MI355X (gfx950), after "Q8BERT: Quantized 8Bit BERT"
+ * (arxiv 1910.06188).  C ABI; every kernel behind it is hand-written HIP.
+ *
+ * Conventions shared by all entry points
+ *   - Every pointer is a DEVICE pointer owned by the caller unless a comment says
+ *     "host".  The library never allocates, frees or keeps a pointer.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     only enqueue work on it: no host synchronisation, no host read of device data.
+ *     Data-dependent scalars (abs-max, scales) therefore live in device memory so
+ *     calls chain on a stream without a round trip.
+ *   - The return value reports what the host can see before launching (null
+ *     pointers, shapes, alignment, launch failure).  Data-dependent problems are
+ *     reported through device flags where stated.
+ *   - Results are deterministic: same bytes in, same bytes out.
+ *   - Inputs must be finite; NaN/Inf give unspecified codes (the method has no
+ *     meaning for them).
+ *   - Tensors are dense row-major.  Activations x[M,K], weights w[N,K]
+ *     (the layer computes x w^T + b), outputs y[M,N].
+ *   - M is the highest quantized value of Eq. 2: 127 for int8 codes, 2^31-1 for
+ *     the int32 bias.
+ */
+#ifndef Q8_H
+#define Q8_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    Q8_OK = 0,
+    Q8_ERR_NULL = 1,   /* a required pointer is NULL */
+    Q8_ERR_SHAPE = 2,  /* negative size, K above Q8_MAX_K, n_groups not dividing N, tensor above 2^32-1 bytes */
+    Q8_ERR_ALIGN = 3,  /* a pointer breaks the alignment its type needs (4 bytes for float/int32) */
+    Q8_ERR_FLAGS = 4,  /* unknown epilogue bit, or a flag without the pointer it needs */
+    Q8_ERR_LAUNCH = 5  /* the HIP runtime refused a launch */
+} q8_status;
+
+/* Largest reduction length: 128*128*K must stay below 2^31 so that no int8 input,
+ * -128 included, can overflow the int32 accumulator before the bias is added. */
+#define Q8_MAX_K 131071
+
+/* q8_linear epilogue bits. */
+#define Q8_EPI_GELU 1u     /* y <- gelu(y), exact-erf form, in fp32 (GELU stays FP32: Section 3) */
+#define Q8_EPI_ABSMAX 2u   /* out_amax[0] <- max(out_amax[0], max|y|) over the fp32 outputs of this call */
+#define Q8_EPI_REQUANT 4u  /* y is written as int8 codes Quantize(y | next_scale[0], 127) instead of fp32 */
+
+/*
+ * Abs-max and scale of a whole tensor: Eq. 3, S = M / max|x| with M = 127, which
+ * Section 4.1 (dynamic quantization) also applies to each incoming activation tensor.
+ *   x          fp32[n], any shape flattened; n >= 0 (n = 0 behaves as all zeros).
+ *   amax_out   fp32[1], required: receives max_i |x_i|.
+ *   scale_out  fp32[1] or NULL: receives 127 / amax as one binary32 division, or 1.0
+ *              when amax is 0 (every code is then 0).
+ * The previous contents of both outputs are ignored.
+ */
+q8_status q8_absmax(const float* x, int64_t n, float* amax_out, float* scale_out, void* stream);
+
+/*
+ * Scale from an abs-max that is already on the device (for instance the one the
+ * Q8_EPI_ABSMAX epilogue of the previous layer produced): scale_out[0] = 127 / amax[0],
+ * 1.0 when amax[0] is 0.  Eq. 3.
+ */
+q8_status q8_scale_from_amax(const float* amax, float* scale_out, void* stream);
+
+/*
+ * Eq. 1: q[i] = Clamp(round(x[i] * scale[0]), -127, 127).  The product is one
+ * binary32 multiply; round is to nearest with ties away from zero; -128 is never
+ * produced.
+ *   x fp32[n]; scale fp32[1] on the device (dynamic from q8_absmax, or a stored
+ *   constant as in Eq. 4); q int8[n]; n >= 0.
+ */
+q8_status q8_quantize(const float* x, int64_t n, const float* scale, int8_t* q, void* stream);
+
+/*
+ * The quantized FC layer at inference (Section 3): Int8 x Int8 GEMM accumulated in
+ * Int32 onto the Int32 bias, then dequantized for the FP32 consumers.
+ *     bq[n]    = Clamp(round(bias[n] * (sx * sw[g(n)])), -(2^31-1), 2^31-1)   (0 if bias is NULL)
+ *     acc[m,n] = bq[n] + sum_k xq[m,k] * wq[n,k]                              (exact int32)
+ *     y[m,n]   = acc[m,n] / (sx * sw[g(n)])                                   (fp32, within 1e-6 relative)
+ *   xq int8[M,K], wq int8[N,K]; bias fp32[N] or NULL.
+ *   sx fp32[1]: activation scale.  sw fp32[n_groups]: weight scale per column group;
+ *   the N columns are split evenly, g(n) = n / (N / n_groups).  n_groups = 1 is the
+ *   paper's layer; 3 packs the Q, K and V projections, each keeping its own S_W.
+ *   y: fp32[M,N], or int8[M,N] with Q8_EPI_REQUANT (then next_scale fp32[1] is required).
+ *   acc_out: int32[M,N] or NULL -- dump of the post-bias accumulator, for parity checks.
+ *   out_amax: fp32[1], required with Q8_EPI_ABSMAX; the caller sets it to 0 beforehand.
+ *   Epilogue order: dequantize, GELU, abs-max, requantize.
+ * M, N >= 0 (either 0: nothing is written); 0 <= K <= Q8_MAX_K; sizes are otherwise
+ * free -- shapes with K % 128 == 0 and 16-byte aligned xq/wq take the MFMA kernel,
+ * anything else a slower generic kernel with identical results.
+ * bq + sum must fit int32 (it wraps otherwise; unreachable for BERT-sized biases).
+ */
+q8_status q8_linear(const int8_t* xq, const int8_t* wq, const float* bias,
+                    const float* sx, const float* sw, int n_groups,
+                    int64_t M, int64_t N, int64_t K,
+                    void* y, int32_t* acc_out, float* out_amax, const float* next_scale,
+                    uint32_t epilogue_flags, void* stream);
+
+/*
+ * Dynamic-quantization FC layer in one call (Section 4.1): abs-max of x, S_x = 127/max,
+ * quantize, then q8_linear.  Same results as calling the three entry points in turn.
+ *   x fp32[M,K]; xq_work int8[M*K] and scal_work fp32[2] are caller-provided scratch
+ *   (on return scal_work[0] = max|x|, scal_work[1] = S_x, xq_work = the int8 codes).
+ *   Other arguments as q8_linear.
+ */
+q8_status q8_linear_f32(const float* x, const int8_t* wq, const float* bias,
+                        const float* sw, int n_groups,
+                        int64_t M, int64_t N, int64_t K,
+                        int8_t* xq_work, float* scal_work,
+                        void* y, int32_t* acc_out, float* out_amax, const float* next_scale,
+                        uint32_t epilogue_flags, void* stream);
+
+/*
+ * The quantized Embedding layer at inference (Section 3): returns the Int8 rows,
+ * or the rows divided by the table's scale for the FP32 sum + LayerNorm that follow.
+ *   table int8[V,H]; scale fp32[1] (ignored when out_is_int8); ids int32[T].
+ *   out: int8[T,H] if out_is_int8, else fp32[T,H] with out[t,h] = table[ids[t],h] / scale[0].
+ *   err_flag: int32[1] or NULL, zeroed by the caller.  An id outside [0,V) writes a
+ *   zero row and sets err_flag[0] = 1; nothing is ever read out of bounds.
+ */
+q8_status q8_embedding(const int8_t* table, const float* scale, int64_t V, int64_t H,
+                       const int32_t* ids, int64_t T, void* out, int out_is_int8,
+                       int32_t* err_flag, void* stream);
+
+/*
+ * BERT's input embedding from three int8 tables, each with its own scale
+ * (Section 3: all Embedding layers are quantized): out[t,:] =
+ * (word[wid[t]]/s[0] + pos[pid[t]]/s[1]) + type[tid[t]]/s[2], fp32[T,H].
+ *   scales fp32[3]; tables int8[Vw,H], int8[Vp,H], int8[Vt,H]; ids int32[T] each.
+ *   Bad ids as in q8_embedding (the whole output row is zero).
+ */
+q8_status q8_embedding_sum3(const int8_t* word, int64_t Vw, const int8_t* pos, int64_t Vp,
+                            const int8_t* type, int64_t Vt, const float* scales, int64_t H,
+                            const int32_t* wid, const int32_t* pid, const int32_t* tid, int64_t T,
+                            float* out, int32_t* err_flag, void* stream);
+
+/* Library version string and a short text for a status code (host pointers, static storage). */
+const char* q8_version(void);
+const char* q8_status_str(q8_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* Q8_H */

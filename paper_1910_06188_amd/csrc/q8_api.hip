@@ -1,0 +1,153 @@
+// C ABI of the q8 library: argument checks, then launches.  See include/q8.h for the
+// contract of every entry point.
+#include "q8.h"
+#include "q8_launch.h"
+
+namespace {
+
+inline bool misaligned(const void* p, unsigned a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+const unsigned kKnownFlags = Q8_EPI_GELU | Q8_EPI_ABSMAX | Q8_EPI_REQUANT;
+
+q8_status check_linear(const int8_t* xq, const int8_t* wq, const float* bias, const float* sx, const float* sw,
+                       int n_groups, int64_t M, int64_t N, int64_t K, void* y, int32_t* acc_out, float* out_amax,
+                       const float* next_scale, uint32_t flags)
+{
+    if (M < 0 || N < 0 || K < 0 || K > Q8_MAX_K || n_groups < 1) return Q8_ERR_SHAPE;
+    if (N % n_groups != 0) return Q8_ERR_SHAPE;
+    if (flags & ~kKnownFlags) return Q8_ERR_FLAGS;
+    if ((flags & Q8_EPI_ABSMAX) && !out_amax) return Q8_ERR_FLAGS;
+    if ((flags & Q8_EPI_REQUANT) && !next_scale) return Q8_ERR_FLAGS;
+    if (M == 0 || N == 0) return Q8_OK;
+    if (!sx || !sw || !y) return Q8_ERR_NULL;
+    if (K > 0 && (!xq || !wq)) return Q8_ERR_NULL;
+    if (misaligned(bias, 4) || misaligned(sx, 4) || misaligned(sw, 4) || misaligned(acc_out, 4) ||
+        misaligned(out_amax, 4) || misaligned(next_scale, 4))
+        return Q8_ERR_ALIGN;
+    if (!(flags & Q8_EPI_REQUANT) && misaligned(y, 4)) return Q8_ERR_ALIGN;
+    if ((M * N + 255) / 256 > 0x7fffffffLL) return Q8_ERR_SHAPE;
+    return Q8_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+q8_status q8_absmax(const float* x, int64_t n, float* amax_out, float* scale_out, void* stream)
+{
+    if (n < 0) return Q8_ERR_SHAPE;
+    if (!amax_out || (n > 0 && !x)) return Q8_ERR_NULL;
+    if (amax_out == scale_out) return Q8_ERR_NULL;
+    if (misaligned(x, 4) || misaligned(amax_out, 4) || misaligned(scale_out, 4)) return Q8_ERR_ALIGN;
+    return q8::launch_absmax(x, n, amax_out, scale_out, as_stream(stream)) ? Q8_ERR_LAUNCH : Q8_OK;
+}
+
+q8_status q8_scale_from_amax(const float* amax, float* scale_out, void* stream)
+{
+    if (!amax || !scale_out) return Q8_ERR_NULL;
+    if (misaligned(amax, 4) || misaligned(scale_out, 4)) return Q8_ERR_ALIGN;
+    return q8::launch_scale_from_amax(amax, scale_out, as_stream(stream)) ? Q8_ERR_LAUNCH : Q8_OK;
+}
+
+q8_status q8_quantize(const float* x, int64_t n, const float* scale, int8_t* q, void* stream)
+{
+    if (n < 0) return Q8_ERR_SHAPE;
+    if (n == 0) return Q8_OK;
+    if (!x || !scale || !q) return Q8_ERR_NULL;
+    if (misaligned(x, 4) || misaligned(scale, 4)) return Q8_ERR_ALIGN;
+    return q8::launch_quantize(x, n, scale, q, as_stream(stream)) ? Q8_ERR_LAUNCH : Q8_OK;
+}
+
+q8_status q8_linear(const int8_t* xq, const int8_t* wq, const float* bias, const float* sx, const float* sw,
+                    int n_groups, int64_t M, int64_t N, int64_t K, void* y, int32_t* acc_out, float* out_amax,
+                    const float* next_scale, uint32_t flags, void* stream)
+{
+    q8_status s = check_linear(xq, wq, bias, sx, sw, n_groups, M, N, K, y, acc_out, out_amax, next_scale, flags);
+    if (s != Q8_OK || M == 0 || N == 0) return s;
+    q8::Epilogue ep;
+    ep.bias = bias;
+    ep.sx = sx;
+    ep.sw = sw;
+    ep.n_groups = n_groups;
+    ep.cols_per_group = (int)(N / n_groups);
+    ep.y = y;
+    ep.acc_out = acc_out;
+    ep.out_amax = out_amax;
+    ep.next_scale = next_scale;
+    ep.flags = flags;
+    int rc = q8::gemm_mfma_eligible(xq, wq, M, N, K)
+                 ? q8::launch_gemm_mfma(xq, wq, M, N, K, ep, as_stream(stream))
+                 : q8::launch_gemm_generic(xq, wq, M, N, K, ep, as_stream(stream));
+    return rc ? Q8_ERR_LAUNCH : Q8_OK;
+}
+
+q8_status q8_linear_f32(const float* x, const int8_t* wq, const float* bias, const float* sw, int n_groups, int64_t M,
+                        int64_t N, int64_t K, int8_t* xq_work, float* scal_work, void* y, int32_t* acc_out,
+                        float* out_amax, const float* next_scale, uint32_t flags, void* stream)
+{
+    if (!scal_work) return Q8_ERR_NULL;
+    if (misaligned(scal_work, 4)) return Q8_ERR_ALIGN;
+    q8_status s = check_linear(xq_work, wq, bias, scal_work + 1, sw, n_groups, M, N, K, y, acc_out, out_amax,
+                               next_scale, flags);
+    if (s != Q8_OK) return s;
+    if (M > 0 && K > 0 && (!x || !xq_work)) return Q8_ERR_NULL;
+    if (misaligned(x, 4)) return Q8_ERR_ALIGN;
+    s = q8_absmax(x, M * K, scal_work, scal_work + 1, stream);
+    if (s != Q8_OK) return s;
+    s = q8_quantize(x, M * K, scal_work + 1, xq_work, stream);
+    if (s != Q8_OK) return s;
+    return q8_linear(xq_work, wq, bias, scal_work + 1, sw, n_groups, M, N, K, y, acc_out, out_amax, next_scale, flags,
+                     stream);
+}
+
+q8_status q8_embedding(const int8_t* table, const float* scale, int64_t V, int64_t H, const int32_t* ids, int64_t T,
+                       void* out, int out_is_int8, int32_t* err_flag, void* stream)
+{
+    if (V < 0 || H < 0 || T < 0) return Q8_ERR_SHAPE;
+    if (T == 0 || H == 0) return Q8_OK;
+    if (!ids || !out || (V > 0 && !table) || (!out_is_int8 && !scale)) return Q8_ERR_NULL;
+    if (misaligned(ids, 4) || misaligned(err_flag, 4) || misaligned(scale, 4)) return Q8_ERR_ALIGN;
+    if (!out_is_int8 && misaligned(out, 4)) return Q8_ERR_ALIGN;
+    if ((T * H + 255) / 256 > 0x7fffffffLL) return Q8_ERR_SHAPE;
+    return q8::launch_embedding(table, scale, V, H, ids, T, out, out_is_int8, err_flag, as_stream(stream))
+               ? Q8_ERR_LAUNCH
+               : Q8_OK;
+}
+
+q8_status q8_embedding_sum3(const int8_t* word, int64_t Vw, const int8_t* pos, int64_t Vp, const int8_t* type,
+                            int64_t Vt, const float* scales, int64_t H, const int32_t* wid, const int32_t* pid,
+                            const int32_t* tid, int64_t T, float* out, int32_t* err_flag, void* stream)
+{
+    if (Vw < 0 || Vp < 0 || Vt < 0 || H < 0 || T < 0) return Q8_ERR_SHAPE;
+    if (T == 0 || H == 0) return Q8_OK;
+    if (!wid || !pid || !tid || !out || !scales) return Q8_ERR_NULL;
+    if ((Vw > 0 && !word) || (Vp > 0 && !pos) || (Vt > 0 && !type)) return Q8_ERR_NULL;
+    if (misaligned(wid, 4) || misaligned(pid, 4) || misaligned(tid, 4) || misaligned(out, 4) ||
+        misaligned(scales, 4) || misaligned(err_flag, 4))
+        return Q8_ERR_ALIGN;
+    if ((T * H + 255) / 256 > 0x7fffffffLL) return Q8_ERR_SHAPE;
+    return q8::launch_embedding_sum3(word, Vw, pos, Vp, type, Vt, scales, H, wid, pid, tid, T, out, err_flag,
+                                     as_stream(stream))
+               ? Q8_ERR_LAUNCH
+               : Q8_OK;
+}
+
+const char* q8_version(void) { return "q8 0.1.0 (gfx950)"; }
+
+const char* q8_status_str(q8_status s)
+{
+    switch (s) {
+        case Q8_OK: return "ok";
+        case Q8_ERR_NULL: return "null pointer";
+        case Q8_ERR_SHAPE: return "bad shape";
+        case Q8_ERR_ALIGN: return "misaligned pointer";
+        case Q8_ERR_FLAGS: return "bad epilogue flags";
+        case Q8_ERR_LAUNCH: return "launch failed";
+    }
+    return "unknown status";
+}
+
+/* Tuning hook for the benchmark (not part of the method): pick the MFMA tile variant, 0 = automatic. */
+void q8_debug_set_gemm_variant(int v) { q8::set_gemm_variant(v); }
+
+}  // extern "C"

@@ -1,0 +1,48 @@
+// Host-side launchers behind the C ABI.  Each returns 0 on success, 1 if the HIP
+// runtime refused a launch.  Arguments are already validated by the callers in
+// q8_api.hip; all pointers are device pointers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace q8 {
+
+// Everything the GEMM epilogue needs (Section 3: Int32 bias, dequantize; optional
+// fp32 GELU, abs-max of the outputs, requantize with a stored scale).
+struct Epilogue {
+    const float* bias;        // fp32[N] or null
+    const float* sx;          // fp32[1]
+    const float* sw;          // fp32[n_groups]
+    int n_groups;
+    int cols_per_group;       // N / n_groups
+    void* y;                  // fp32[M,N] or int8[M,N] (requant)
+    int32_t* acc_out;         // int32[M,N] or null
+    float* out_amax;          // fp32[1] or null
+    const float* next_scale;  // fp32[1] or null
+    unsigned flags;
+};
+
+int launch_absmax(const float* x, int64_t n, float* amax_out, float* scale_out, hipStream_t st);
+int launch_scale_from_amax(const float* amax, float* scale_out, hipStream_t st);
+int launch_quantize(const float* x, int64_t n, const float* scale, int8_t* q, hipStream_t st);
+
+// True when the MFMA kernel can take the problem (K % 128 == 0, K >= 128, 16-byte
+// aligned operands, each operand below 2^32 bytes).
+bool gemm_mfma_eligible(const int8_t* xq, const int8_t* wq, int64_t M, int64_t N, int64_t K);
+int launch_gemm_mfma(const int8_t* xq, const int8_t* wq, int64_t M, int64_t N, int64_t K, const Epilogue& ep,
+                     hipStream_t st);
+int launch_gemm_generic(const int8_t* xq, const int8_t* wq, int64_t M, int64_t N, int64_t K, const Epilogue& ep,
+                        hipStream_t st);
+
+int launch_embedding(const int8_t* table, const float* scale, int64_t V, int64_t H, const int32_t* ids, int64_t T,
+                     void* out, int out_is_int8, int32_t* err_flag, hipStream_t st);
+int launch_embedding_sum3(const int8_t* word, int64_t Vw, const int8_t* pos, int64_t Vp, const int8_t* type,
+                          int64_t Vt, const float* scales, int64_t H, const int32_t* wid, const int32_t* pid,
+                          const int32_t* tid, int64_t T, float* out, int32_t* err_flag, hipStream_t st);
+
+// Tuning hook used by the benchmark and tests: selects the MFMA tile variant
+// (0 = automatic choice from the shape).
+void set_gemm_variant(int v);
+int get_gemm_variant();
+
+}  // namespace q8

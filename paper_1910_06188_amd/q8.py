@@ -1,0 +1,152 @@
+"""Thin ctypes binding over libq8.so (the C ABI declared in include/q8.h).
+
+Argument marshalling only: every step of the quantized FC layer runs in the HIP
+kernels behind the library.  PyTorch supplies device memory and the stream.
+Importing this module fails loudly when the library has not been built
+(`python -m paper_1910_06188_amd.build`); there is no CPU or PyTorch fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libq8.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build the HIP library first (python -m paper_1910_06188_amd.build). "
+        "There is no fallback path.")
+
+_lib = C.CDLL(LIB_PATH)
+
+OK = 0
+EPI_GELU, EPI_ABSMAX, EPI_REQUANT = 1, 2, 4
+MAX_K = 131071
+
+_vp, _i64, _i32, _u32 = C.c_void_p, C.c_int64, C.c_int, C.c_uint32
+
+_lib.q8_absmax.argtypes = [_vp, _i64, _vp, _vp, _vp]
+_lib.q8_scale_from_amax.argtypes = [_vp, _vp, _vp]
+_lib.q8_quantize.argtypes = [_vp, _i64, _vp, _vp, _vp]
+_lib.q8_linear.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _u32, _vp]
+_lib.q8_linear_f32.argtypes = [_vp, _vp, _vp, _vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _u32, _vp]
+_lib.q8_embedding.argtypes = [_vp, _vp, _i64, _i64, _vp, _i64, _vp, _i32, _vp, _vp]
+_lib.q8_embedding_sum3.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _vp]
+for _f in ("q8_absmax", "q8_scale_from_amax", "q8_quantize", "q8_linear", "q8_linear_f32", "q8_embedding",
+           "q8_embedding_sum3"):
+    getattr(_lib, _f).restype = C.c_int
+_lib.q8_version.restype = C.c_char_p
+_lib.q8_status_str.restype = C.c_char_p
+_lib.q8_status_str.argtypes = [C.c_int]
+_lib.q8_debug_set_gemm_variant.argtypes = [C.c_int]
+_lib.q8_debug_set_gemm_variant.restype = None
+
+
+class Q8Error(RuntimeError):
+    def __init__(self, code: int, where: str):
+        super().__init__(f"{where}: {_lib.q8_status_str(code).decode()} (status {code})")
+        self.code = code
+
+
+def _ck(code: int, where: str) -> None:
+    if code != OK:
+        raise Q8Error(code, where)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("q8 takes device tensors")
+    if not t.is_contiguous():
+        raise ValueError("q8 takes contiguous tensors")
+    return t.data_ptr()
+
+
+def _stream(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def version() -> str:
+    return _lib.q8_version().decode()
+
+
+def status_str(code: int) -> str:
+    return _lib.q8_status_str(code).decode()
+
+
+def set_gemm_variant(v: int) -> None:
+    _lib.q8_debug_set_gemm_variant(int(v))
+
+
+def q8_absmax(x, amax_out, scale_out=None, stream=None) -> None:
+    """amax_out[0] = max|x|, scale_out[0] = 127/amax (Eq. 3)."""
+    _ck(_lib.q8_absmax(_ptr(x), x.numel(), _ptr(amax_out), _ptr(scale_out), _stream(stream)), "q8_absmax")
+
+
+def q8_scale_from_amax(amax, scale_out, stream=None) -> None:
+    _ck(_lib.q8_scale_from_amax(_ptr(amax), _ptr(scale_out), _stream(stream)), "q8_scale_from_amax")
+
+
+def q8_quantize(x, scale, q, stream=None) -> None:
+    """q = Clamp(round(x * scale), -127, 127) (Eq. 1)."""
+    if q.numel() != x.numel():
+        raise ValueError("q8_quantize: q and x differ in size")
+    _ck(_lib.q8_quantize(_ptr(x), x.numel(), _ptr(scale), _ptr(q), _stream(stream)), "q8_quantize")
+
+
+def q8_linear(xq, wq, bias, sx, sw, y, n_groups=1, acc_out=None, out_amax=None, next_scale=None, flags=0,
+              stream=None) -> None:
+    """y = dequant(xq wq^T + quantized bias) (Section 3), optional fused epilogue stages."""
+    M, K = xq.shape
+    N, K2 = wq.shape
+    if K != K2 or y.numel() != M * N or (acc_out is not None and acc_out.numel() != M * N):
+        raise ValueError("q8_linear: shape mismatch")
+    if sw.numel() != n_groups or (bias is not None and bias.numel() != N):
+        raise ValueError("q8_linear: scale/bias size mismatch")
+    _ck(_lib.q8_linear(_ptr(xq), _ptr(wq), _ptr(bias), _ptr(sx), _ptr(sw), n_groups, M, N, K, _ptr(y),
+                       _ptr(acc_out), _ptr(out_amax), _ptr(next_scale), flags, _stream(stream)), "q8_linear")
+
+
+def q8_linear_f32(x, wq, bias, sw, xq_work, scal_work, y, n_groups=1, acc_out=None, out_amax=None, next_scale=None,
+                  flags=0, stream=None) -> None:
+    """Dynamic-quantization FC layer in one call: abs-max, quantize, GEMM, dequantize."""
+    M, K = x.shape
+    N, K2 = wq.shape
+    if K != K2 or y.numel() != M * N or xq_work.numel() < M * K or scal_work.numel() < 2:
+        raise ValueError("q8_linear_f32: shape mismatch")
+    if sw.numel() != n_groups or (bias is not None and bias.numel() != N):
+        raise ValueError("q8_linear_f32: scale/bias size mismatch")
+    _ck(_lib.q8_linear_f32(_ptr(x), _ptr(wq), _ptr(bias), _ptr(sw), n_groups, M, N, K, _ptr(xq_work),
+                           _ptr(scal_work), _ptr(y), _ptr(acc_out), _ptr(out_amax), _ptr(next_scale), flags,
+                           _stream(stream)), "q8_linear_f32")
+
+
+def q8_embedding(table, scale, ids, out, err_flag=None, stream=None) -> None:
+    """out[t] = table[ids[t]] (int8 out) or table[ids[t]] / scale (fp32 out)."""
+    V, H = table.shape
+    T = ids.numel()
+    if out.numel() != T * H:
+        raise ValueError("q8_embedding: shape mismatch")
+    out_is_int8 = 1 if out.dtype == torch.int8 else 0
+    _ck(_lib.q8_embedding(_ptr(table), _ptr(scale), V, H, _ptr(ids), T, _ptr(out), out_is_int8, _ptr(err_flag),
+                          _stream(stream)), "q8_embedding")
+
+
+def q8_embedding_sum3(word, pos, typ, scales, wid, pid, tid, out, err_flag=None, stream=None) -> None:
+    H = word.shape[1]
+    T = wid.numel()
+    if pos.shape[1] != H or typ.shape[1] != H or out.numel() != T * H or pid.numel() != T or tid.numel() != T:
+        raise ValueError("q8_embedding_sum3: shape mismatch")
+    _ck(_lib.q8_embedding_sum3(_ptr(word), word.shape[0], _ptr(pos), pos.shape[0], _ptr(typ), typ.shape[0],
+                               _ptr(scales), H, _ptr(wid), _ptr(pid), _ptr(tid), T, _ptr(out), _ptr(err_flag),
+                               _stream(stream)), "q8_embedding_sum3")
+
+
+def raw():
+    """The ctypes library handle, for tests that call the C ABI with unusual arguments."""
+    return _lib

@@ -1,0 +1,83 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header
+declares, and rejects bad arguments on the host before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "q8.h")
+LIB = os.path.join(ROOT, "paper_1910_06188_amd", "libq8.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_1910_06188_amd import build
+        build.build()
+    return C.CDLL(LIB)
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(q8_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_four_named_calls():
+    names = declared_functions()
+    for n in ("q8_absmax", "q8_quantize", "q8_linear", "q8_embedding"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for n in declared_functions():
+        assert hasattr(lib, n), n
+
+
+def test_version_and_status_strings(lib):
+    lib.q8_version.restype = C.c_char_p
+    lib.q8_status_str.restype = C.c_char_p
+    assert b"gfx950" in lib.q8_version()
+    texts = {lib.q8_status_str(i) for i in range(6)}
+    assert len(texts) == 6
+
+
+def test_host_side_argument_checks(lib):
+    vp, i64 = C.c_void_p, C.c_int64
+    lib.q8_absmax.argtypes = [vp, i64, vp, vp, vp]
+    lib.q8_quantize.argtypes = [vp, i64, vp, vp, vp]
+    lib.q8_linear.argtypes = [vp, vp, vp, vp, vp, C.c_int, i64, i64, i64, vp, vp, vp, vp, C.c_uint32, vp]
+    lib.q8_embedding.argtypes = [vp, vp, i64, i64, vp, i64, vp, C.c_int, vp, vp]
+    OK, NULL, SHAPE, ALIGN, FLAGS = 0, 1, 2, 3, 4
+    p = 0x1000  # never dereferenced on the host
+    assert lib.q8_absmax(p, -1, p, p + 4, None) == SHAPE
+    assert lib.q8_absmax(None, 8, p, p + 4, None) == NULL
+    assert lib.q8_absmax(p, 8, None, p + 4, None) == NULL
+    assert lib.q8_absmax(p + 2, 8, p, p + 4, None) == ALIGN
+    assert lib.q8_quantize(p, -5, p, p, None) == SHAPE
+    assert lib.q8_quantize(p, 0, None, None, None) == OK          # empty: nothing to do
+    assert lib.q8_quantize(p, 4, None, p, None) == NULL
+    # linear: K above the int32-safe bound, groups not dividing N, unknown flag, flag without its pointer
+    assert lib.q8_linear(p, p, None, p, p, 1, 4, 4, 131072, p, None, None, None, 0, None) == SHAPE
+    assert lib.q8_linear(p, p, None, p, p, 3, 4, 4, 128, p, None, None, None, 0, None) == SHAPE
+    assert lib.q8_linear(p, p, None, p, p, 1, 4, 4, 128, p, None, None, None, 8, None) == FLAGS
+    assert lib.q8_linear(p, p, None, p, p, 1, 4, 4, 128, p, None, None, None, 2, None) == FLAGS
+    assert lib.q8_linear(p, p, None, p, p, 1, 4, 4, 128, p, None, None, None, 4, None) == FLAGS
+    assert lib.q8_linear(p, None, None, p, p, 1, 4, 4, 128, p, None, None, None, 0, None) == NULL
+    assert lib.q8_linear(p, p, None, p, p, 1, 0, 4, 128, p, None, None, None, 0, None) == OK   # M = 0
+    assert lib.q8_linear(p, p, None, p + 2, p, 1, 4, 4, 128, p, None, None, None, 0, None) == ALIGN
+    assert lib.q8_embedding(p, p, 10, 8, None, 4, p, 0, None, None) == NULL
+    assert lib.q8_embedding(p, p, 10, 8, p, 0, p, 0, None, None) == OK                       # T = 0
+    assert lib.q8_embedding(p, p, -1, 8, p, 4, p, 0, None, None) == SHAPE
+
+
+def test_product_package_does_not_reach_the_oracle():
+    """The product path must not import, link or read anything under oracle/."""
+    pkg = os.path.join(ROOT, "paper_1910_06188_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp", ".c")):
+                text = open(os.path.join(dirpath, f), errors="ignore").read()
+                assert not re.search(r"(from|import)\s+oracle|q8_oracle|oracle/|q8o_", text), os.path.join(dirpath, f)

@@ -1,0 +1,493 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle on the same
+seeded inputs.  int8 codes and int32 accumulators must match bit for bit; fp32
+outputs within 1e-6 relative (the accumulator is an exact integer, so the relative
+error of the dequantised value does not depend on magnitude)."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from oracle import q8_oracle as O  # noqa: E402
+from paper_1910_06188_amd import synth  # noqa: E402
+
+RTOL = 1e-6          # fp32 dequantised outputs
+GELU_RTOL, GELU_ATOL = 1e-5, 1e-6   # fp32 erfc on the GPU vs fp64 on the host
+
+
+@pytest.fixture(scope="module")
+def q8():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1910_06188_amd import q8 as mod
+    return mod
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def scalar(v, dtype=torch.float32):
+    return torch.tensor([v], dtype=dtype, device="cuda")
+
+
+def assert_rel(got, ref, rtol=RTOL, atol=0.0):
+    got = got.astype(np.float64)
+    ref = ref.astype(np.float64)
+    err = np.abs(got - ref)
+    tol = atol + rtol * np.abs(ref)
+    bad = err > tol
+    assert not bad.any(), f"{bad.sum()} of {bad.size} outside tolerance; worst rel {np.max(err / np.maximum(np.abs(ref), 1e-30)):.3e}"
+
+
+# --------------------------------------------------------------------------- abs-max / scale
+@pytest.mark.parametrize("n", [0, 1, 3, 4, 5, 63, 64, 255, 1023, 4096, 4099, 1_000_003, 12_582_912])
+def test_absmax_and_scale(q8, n):
+    g = synth.rng(100 + n % 97)
+    x = g.standard_normal(n, dtype=np.float32) * np.float32(2.5)
+    if n > 10:
+        x[g.integers(0, n)] = np.float32(-77.25)      # a negative extreme somewhere
+    xd = dev(x)
+    amax = torch.full((1,), -1.0, device="cuda")
+    sc = torch.full((1,), -1.0, device="cuda")
+    q8.q8_absmax(xd, amax, sc)
+    a_ref = O.absmax(x)
+    assert host(amax)[0] == a_ref
+    assert host(sc)[0] == O.scale(a_ref)
+    # scale optional
+    amax2 = torch.full((1,), -1.0, device="cuda")
+    q8.q8_absmax(xd, amax2, None)
+    assert host(amax2)[0] == a_ref
+
+
+def test_absmax_misaligned_views_and_tail_positions(q8):
+    g = synth.rng(7)
+    base = g.standard_normal(5000, dtype=np.float32)
+    bd = dev(base)
+    for off in (1, 2, 3):
+        for n in (1, 2, 7, 1000, 4993):
+            x = base[off:off + n]
+            amax, sc = scalar(0.0), scalar(0.0)
+            q8.q8_absmax(bd[off:off + n], amax, sc)
+            assert host(amax)[0] == O.absmax(x)
+    # the extreme placed at every position near the vector head/tail boundaries
+    n = 1030
+    for pos in list(range(0, 9)) + list(range(n - 9, n)):
+        x = np.full(n, 0.5, np.float32)
+        x[pos] = -3.0
+        amax = scalar(0.0)
+        q8.q8_absmax(dev(x)[0:n], amax, None)
+        assert host(amax)[0] == 3.0
+    # all zeros: S = 1
+    amax, sc = scalar(-1.0), scalar(-1.0)
+    q8.q8_absmax(torch.zeros(1000, device="cuda"), amax, sc)
+    assert host(amax)[0] == 0.0 and host(sc)[0] == 1.0
+
+
+def test_scale_from_amax(q8):
+    for a in (0.0, 1.0, 5.2173, 127.0, 0.0999, 3e-30):
+        out = scalar(-1.0)
+        q8.q8_scale_from_amax(scalar(a), out)
+        assert host(out)[0] == O.scale(np.float32(a))
+
+
+# --------------------------------------------------------------------------- quantize
+def test_quantize_hand_cases(q8, golden_dir):
+    with open(os.path.join(golden_dir, "quantize_cases.json")) as f:
+        cases = json.load(f)["cases"]
+    for c in cases:
+        x = np.array(c["x"], dtype=np.float32)
+        xd = dev(x)
+        sc = scalar(float(c["scale"]))
+        if c["dynamic"]:
+            amax = scalar(0.0)
+            q8.q8_absmax(xd, amax, sc)
+            assert host(amax)[0] == np.float32(c["amax"]) and host(sc)[0] == np.float32(c["scale"])
+        q = torch.zeros(x.size, dtype=torch.int8, device="cuda")
+        q8.q8_quantize(xd, sc, q)
+        assert host(q).tolist() == c["q"], c["name"]
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 5, 1024, 4097, 999_999, 3_145_728])
+def test_quantize_bit_exact_dynamic(q8, n):
+    g = synth.rng(200 + n % 89)
+    x = g.standard_normal(n, dtype=np.float32)
+    xd = dev(x)
+    amax, sc = scalar(0.0), scalar(0.0)
+    q = torch.empty(n, dtype=torch.int8, device="cuda")
+    q8.q8_absmax(xd, amax, sc)
+    q8.q8_quantize(xd, sc, q)
+    s = O.scale(O.absmax(x))
+    assert host(sc)[0] == s
+    np.testing.assert_array_equal(host(q), O.quantize(x, s))
+
+
+def test_quantize_ties_static_scales_and_misalignment(q8):
+    g = synth.rng(31)
+    for s in (1.0, 0.5, 63.5, 24.413, 1270.5, 0.037):
+        s32 = np.float32(s)
+        ties = (np.arange(-140, 141, dtype=np.float32) + np.float32(0.5)) / s32
+        x = np.concatenate([ties, np.nextafter(ties, np.float32(np.inf)), np.nextafter(ties, np.float32(-np.inf)),
+                            g.standard_normal(5000, dtype=np.float32) * np.float32(100 / s),
+                            np.array([1e10, -1e10, 0.0, -0.0, 1e-40, -1e-40], dtype=np.float32)]).astype(np.float32)
+        xd = dev(x)
+        for off in (0, 1, 2, 3):
+            n = x.size - off - 5
+            qbuf = torch.zeros(x.size + 8, dtype=torch.int8, device="cuda")
+            for qoff in (0, 1):
+                q = qbuf[qoff:qoff + n]
+                q8.q8_quantize(xd[off:off + n], scalar(float(s32)), q)
+                np.testing.assert_array_equal(host(q), O.quantize(x[off:off + n], s32))
+    # writes stay inside q
+    qbuf = torch.full((64,), 99, dtype=torch.int8, device="cuda")
+    q8.q8_quantize(dev(np.ones(13, np.float32)), scalar(5.0), qbuf[8:21])
+    hb = host(qbuf)
+    assert np.all(hb[:8] == 99) and np.all(hb[21:] == 99) and np.all(hb[8:21] == 5)
+
+
+# --------------------------------------------------------------------------- linear
+def run_linear(q8, x, W, b, n_groups=1, flags=0, sx_static=None, next_scale=None, variant=0, Ws=None):
+    """GPU chain absmax -> quantize -> linear through the C ABI; returns host arrays."""
+    M, K = x.shape
+    if Ws is None:
+        Ws = [W]
+    wq_parts, sw_parts = [], []
+    for Wp in Ws:                              # weights: same kernels, offline (Eq. 3 + Eq. 1)
+        wd = dev(Wp)
+        a, s = scalar(0.0), scalar(0.0)
+        q8.q8_absmax(wd, a, s)
+        wq = torch.empty(Wp.shape, dtype=torch.int8, device="cuda")
+        q8.q8_quantize(wd, s, wq)
+        wq_parts.append(wq)
+        sw_parts.append(s)
+    wq = torch.cat(wq_parts, 0).contiguous()
+    sw = torch.cat(sw_parts).contiguous()
+    N = wq.shape[0]
+    xd = dev(x)
+    amax, sx = scalar(0.0), scalar(0.0)
+    if sx_static is None:
+        q8.q8_absmax(xd, amax, sx)
+    else:
+        sx = scalar(float(sx_static))
+    xq = torch.empty((M, K), dtype=torch.int8, device="cuda")
+    q8.q8_quantize(xd, sx, xq)
+    y = torch.empty((M, N), dtype=torch.int8 if flags & 4 else torch.float32, device="cuda")
+    acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    out_amax = scalar(0.0)
+    ns = None if next_scale is None else scalar(float(next_scale))
+    q8.set_gemm_variant(variant)
+    try:
+        q8.q8_linear(xq, wq, None if b is None else dev(b), sx, sw, y, n_groups=n_groups, acc_out=acc,
+                     out_amax=out_amax if flags & 2 else None, next_scale=ns, flags=flags)
+        y2 = None
+        if flags == 0:                                    # the dedicated fp32-only kernel as well
+            y2 = torch.empty((M, N), dtype=torch.float32, device="cuda")
+            q8.q8_linear(xq, wq, None if b is None else dev(b), sx, sw, y2, n_groups=n_groups)
+    finally:
+        q8.set_gemm_variant(0)
+    torch.cuda.synchronize()
+    return dict(xq=host(xq), wq=host(wq), sw=host(sw), sx=host(sx)[0], acc=host(acc), y=host(y),
+                y_plain=None if y2 is None else host(y2), out_amax=host(out_amax)[0])
+
+
+def check_linear(r, x, b, act_gelu=False, sx_static=None, threads=8):
+    """Oracle on the same inputs; weights' codes are checked against the oracle too."""
+    ref = O.linear(x, r["wq"], r["sw"], b, sx=sx_static, act_gelu=False, threads=threads)
+    assert r["sx"] == ref["sx"]
+    np.testing.assert_array_equal(r["xq"], ref["xq"])
+    np.testing.assert_array_equal(r["acc"], ref["acc"])
+    return ref
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4])
+def test_linear_single_fc_config(q8, variant):
+    d = synth.single_fc(0)                                  # 16 x 768 -> 768
+    r = run_linear(q8, d["x"], d["W"], d["b"], variant=variant)
+    wq_ref, sw_ref = O.quantize_tensor(d["W"])
+    np.testing.assert_array_equal(r["wq"], wq_ref)
+    assert r["sw"][0] == sw_ref
+    ref = check_linear(r, d["x"], d["b"])
+    assert_rel(r["y"], ref["y"])
+    assert_rel(r["y_plain"], ref["y"])
+
+
+@pytest.mark.parametrize("M,K,N,variant", [
+    (300, 256, 520, 0), (700, 384, 600, 1), (700, 384, 600, 2), (700, 384, 600, 3), (700, 384, 600, 4),
+    (257, 128, 129, 1), (1, 128, 1, 3), (513, 1024, 257, 2), (255, 640, 1000, 4), (1030, 256, 2100, 1),
+])
+def test_linear_mfma_ragged_multi_tile(q8, M, K, N, variant):
+    d = synth.fc_layer(1000 + M + N, M, K, N)
+    r = run_linear(q8, d["x"], d["W"], d["b"], variant=variant)
+    ref = check_linear(r, d["x"], d["b"])
+    assert_rel(r["y"], ref["y"])
+    assert_rel(r["y_plain"], ref["y"])
+
+
+@pytest.mark.parametrize("M,K,N", [(33, 100, 70), (5, 1, 3), (64, 127, 64), (17, 200, 19), (2, 3000, 2), (40, 0, 8)])
+def test_linear_generic_path_any_shape(q8, M, K, N):
+    d = synth.fc_layer(2000 + M + K, M, max(K, 1), N)
+    x = d["x"][:, :K]
+    W = d["W"][:, :K]
+    if K == 0:                                              # no reduction: y is the dequantised bias
+        xq = torch.empty((M, 0), dtype=torch.int8, device="cuda")
+        wq = torch.empty((N, 0), dtype=torch.int8, device="cuda")
+        y = torch.empty((M, N), device="cuda")
+        acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+        q8.q8_linear(xq, wq, dev(d["b"]), scalar(2.0), scalar(8.0), y, acc_out=acc)
+        bq = O.quantize_bias(d["b"], N, 2.0, [8.0])
+        np.testing.assert_array_equal(host(acc), np.broadcast_to(bq, (M, N)))
+        assert_rel(host(y), O.dequant(np.broadcast_to(bq, (M, N)).copy(), 2.0, [8.0]))
+        return
+    r = run_linear(q8, x, W, d["b"])
+    ref = check_linear(r, x, d["b"])
+    assert_rel(r["y"], ref["y"])
+    assert_rel(r["y_plain"], ref["y"])
+
+
+def test_linear_misaligned_operands_take_generic_path(q8):
+    g = synth.rng(41)
+    M, K, N = 20, 256, 24
+    xq = synth.random_int8(g, (M, K))
+    wq = synth.random_int8(g, (N, K))
+    buf_x = torch.zeros(M * K + 16, dtype=torch.int8, device="cuda")
+    buf_x[1:1 + M * K] = dev(xq).reshape(-1)
+    xv = buf_x[1:1 + M * K].view(M, K)
+    y = torch.empty((M, N), device="cuda")
+    acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    q8.q8_linear(xv, dev(wq), None, scalar(3.0), scalar(7.0), y, acc_out=acc)
+    np.testing.assert_array_equal(host(acc), O.gemm_i8(xq, wq))
+
+
+def test_linear_no_bias_and_grouped_qkv(q8):
+    g = synth.rng(42)
+    M, K, H = 200, 256, 128
+    x = synth.activations(g, M, K)
+    Ws = [synth.weights(g, H, K) * np.float32(f) for f in (1.0, 2.5, 0.3)]
+    b = np.concatenate([synth.bias(g, H) for _ in range(3)])
+    r = run_linear(q8, x, None, b, n_groups=3, Ws=Ws)
+    ref = check_linear(r, x, b)
+    assert_rel(r["y"], ref["y"])
+    assert len(set(r["sw"].tolist())) == 3
+    r0 = run_linear(q8, x, Ws[0], None)
+    ref0 = check_linear(r0, x, None)
+    assert_rel(r0["y"], ref0["y"])
+
+
+def test_linear_int32_exactness_stress(q8):
+    """Sums that are odd and far above 2^24: any floating-point accumulation would miss them."""
+    K = 4096
+    for M, N in ((3, 2), (130, 260)):
+        xq = np.full((M, K), 127, np.int8)
+        wq = np.full((N, K), -127, np.int8)
+        wq[:, 0] = -126                                     # makes the sum odd: -(4095*16129 + 127*126)
+        acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+        y = torch.empty((M, N), device="cuda")
+        q8.q8_linear(dev(xq), dev(wq), None, scalar(1.0), scalar(1.0), y, acc_out=acc)
+        assert np.all(host(acc) == -(4095 * 16129 + 127 * 126))
+        assert_rel(host(y), O.dequant(host(acc), 1.0, [1.0]))
+    # extreme codes incl. -128 at the largest K the MFMA path takes
+    K = 131072 - 128
+    xq = np.full((2, K), -128, np.int8)
+    wq = np.full((2, K), -128, np.int8)
+    acc = torch.empty((2, 2), dtype=torch.int32, device="cuda")
+    y = torch.empty((2, 2), device="cuda")
+    q8.q8_linear(dev(xq), dev(wq), None, scalar(1.0), scalar(1.0), y, acc_out=acc)
+    assert np.all(host(acc) == 16384 * K)
+    # alternating signs cancel exactly
+    K = 1024
+    alt = np.where(np.arange(K) % 2 == 0, 127, -127).astype(np.int8)
+    acc = torch.empty((1, 1), dtype=torch.int32, device="cuda")
+    q8.q8_linear(dev(alt[None, :]), dev(np.full((1, K), 127, np.int8)), None, scalar(1.0), scalar(1.0),
+                 torch.empty((1, 1), device="cuda"), acc_out=acc)
+    assert host(acc)[0, 0] == 0
+
+
+def test_linear_random_int8_all_variants_asymmetric(q8):
+    """Raw int8 operands (no quantize step): pins the MFMA operand and accumulator layout."""
+    g = synth.rng(43)
+    M, K, N = 290, 384, 410
+    xq = synth.random_int8(g, (M, K), -128, 127)
+    wq = synth.random_int8(g, (N, K), -128, 127)
+    ref = O.gemm_i8(xq, wq, threads=8)
+    for variant in (1, 2, 3, 4):
+        q8.set_gemm_variant(variant)
+        try:
+            acc = torch.zeros((M, N), dtype=torch.int32, device="cuda")
+            q8.q8_linear(dev(xq), dev(wq), None, scalar(1.0), scalar(1.0), torch.empty((M, N), device="cuda"),
+                         acc_out=acc)
+        finally:
+            q8.set_gemm_variant(0)
+        np.testing.assert_array_equal(host(acc), ref, err_msg=f"variant {variant}")
+
+
+def test_linear_bias_saturation(q8):
+    with open(os.path.join(os.path.dirname(__file__), "golden", "bias_cases.json")) as f:
+        cases = json.load(f)["cases"]
+    for c in cases:
+        b = np.array(c["b"], np.float32)
+        N = b.size
+        K = 128
+        acc = torch.empty((1, N), dtype=torch.int32, device="cuda")
+        q8.q8_linear(torch.zeros((1, K), dtype=torch.int8, device="cuda"),
+                     torch.zeros((N, K), dtype=torch.int8, device="cuda"), dev(b), scalar(c["sx"]),
+                     dev(np.array(c["sw"], np.float32)), torch.empty((1, N), device="cuda"),
+                     n_groups=len(c["sw"]), acc_out=acc)
+        assert host(acc)[0].tolist() == c["bq"], c["name"]
+
+
+def test_linear_zero_input_tensor(q8):
+    d = synth.fc_layer(44, 130, 256, 140)
+    x = np.zeros_like(d["x"])
+    r = run_linear(q8, x, d["W"], d["b"])
+    assert r["sx"] == 1.0 and not r["xq"].any()
+    ref = check_linear(r, x, d["b"])
+    assert_rel(r["y"], ref["y"])
+
+
+@pytest.mark.parametrize("M,K,N", [(300, 256, 520), (33, 100, 70)])
+def test_linear_epilogue_gelu_absmax_requant(q8, M, K, N):
+    d = synth.fc_layer(45 + M, M, K, N)
+    x, W, b = d["x"], d["W"] * np.float32(8.0), d["b"]
+    # GELU + abs-max, fp32 out
+    r = run_linear(q8, x, W, b, flags=1 | 2)
+    ref = check_linear(r, x, b)
+    gl = O.gelu(ref["y"])
+    assert_rel(r["y"], gl, rtol=GELU_RTOL, atol=GELU_ATOL)
+    assert r["out_amax"] == np.abs(r["y"]).max()           # abs-max of the values the GPU itself wrote
+    # abs-max alone on the plain dequantised output
+    r2 = run_linear(q8, x, W, b, flags=2)
+    ref2 = check_linear(r2, x, b)
+    assert_rel(r2["y"], ref2["y"])
+    assert r2["out_amax"] == np.abs(r2["y"]).max()
+    # requantise with a stored scale: codes from the GPU's own fp32 values (stage-wise rule);
+    # against the oracle's fp32 values they may differ by one code only where the product
+    # sits within rounding distance of a tie
+    ns = np.float32(127.0) / np.abs(r2["y"]).max()
+    r3 = run_linear(q8, x, W, b, flags=4, next_scale=ns)
+    check_linear(r3, x, b)
+    np.testing.assert_array_equal(r3["y"], O.quantize(r2["y"], ns))
+    diff = r3["y"].astype(np.int32) - O.quantize(ref2["y"], ns).astype(np.int32)
+    assert np.abs(diff).max() <= 1
+    p = ref2["y"].astype(np.float64) * float(ns)
+    near_tie = np.abs(np.abs(p - np.trunc(p)) - 0.5) < 1e-4 * np.maximum(1.0, np.abs(p))
+    assert np.all(near_tie[diff != 0])
+    # GELU + requant together
+    gmax = np.abs(r["y"]).max()
+    ns2 = np.float32(127.0) / gmax
+    r4 = run_linear(q8, x, W, b, flags=1 | 4, next_scale=ns2)
+    np.testing.assert_array_equal(r4["y"], O.quantize(r["y"], ns2))
+
+
+def test_linear_static_activation_scale(q8):
+    d = synth.fc_layer(46, 150, 256, 200)
+    sx = np.float32(20.0)                                   # stored scale: values beyond 6.35 saturate
+    r = run_linear(q8, d["x"] * np.float32(2.0), d["W"], d["b"], sx_static=sx)
+    ref = check_linear(r, d["x"] * np.float32(2.0), d["b"], sx_static=sx)
+    assert np.abs(r["xq"]).max() == 127
+    assert_rel(r["y"], ref["y"])
+
+
+def test_linear_f32_one_call_equals_chain(q8):
+    d = synth.fc_layer(47, 260, 384, 300)
+    r = run_linear(q8, d["x"], d["W"], d["b"])
+    M, K = d["x"].shape
+    N = d["W"].shape[0]
+    xq_work = torch.empty(M * K, dtype=torch.int8, device="cuda")
+    scal = torch.zeros(2, device="cuda")
+    y = torch.empty((M, N), device="cuda")
+    acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    q8.q8_linear_f32(dev(d["x"]), dev(r["wq"]), dev(d["b"]), dev(r["sw"]), xq_work, scal, y, acc_out=acc)
+    np.testing.assert_array_equal(host(acc), r["acc"])
+    np.testing.assert_array_equal(host(y), r["y"])
+    np.testing.assert_array_equal(host(xq_work).reshape(M, K), r["xq"])
+    assert host(scal)[1] == r["sx"]
+
+
+def test_linear_is_deterministic(q8):
+    d = synth.fc_layer(48, 600, 512, 700)
+    a = run_linear(q8, d["x"], d["W"], d["b"])
+    b = run_linear(q8, d["x"], d["W"], d["b"])
+    assert a["y"].tobytes() == b["y"].tobytes() and a["acc"].tobytes() == b["acc"].tobytes()
+
+
+def test_linear_empty_shapes(q8):
+    y = torch.full((4,), 7.0, device="cuda")
+    q8.q8_linear(torch.empty((0, 128), dtype=torch.int8, device="cuda"),
+                 torch.empty((4, 128), dtype=torch.int8, device="cuda"), None, scalar(1.0), scalar(1.0), y[:0])
+    q8.q8_quantize(torch.empty(0, device="cuda"), scalar(1.0), torch.empty(0, dtype=torch.int8, device="cuda"))
+    torch.cuda.synchronize()
+    assert np.all(host(y) == 7.0)
+
+
+# --------------------------------------------------------------------------- embedding
+@pytest.mark.parametrize("V,H,T", [(1000, 768, 257), (30522, 768, 4096), (50, 30, 77), (2, 768, 100), (300, 1024, 1)])
+def test_embedding_gather(q8, V, H, T):
+    g = synth.rng(300 + V % 13)
+    E = synth.weights(g, V, H)
+    ed = dev(E)
+    a, s = scalar(0.0), scalar(0.0)
+    q8.q8_absmax(ed, a, s)
+    eq = torch.empty((V, H), dtype=torch.int8, device="cuda")
+    q8.q8_quantize(ed, s, eq)
+    eq_ref, s_ref = O.quantize_tensor(E)
+    np.testing.assert_array_equal(host(eq), eq_ref)
+    ids = g.integers(0, V, size=T, dtype=np.int32)
+    ids[0], ids[-1] = 0, V - 1
+    if T > 4:
+        ids[1] = ids[2] = V - 1
+    out_i8 = torch.empty((T, H), dtype=torch.int8, device="cuda")
+    out_f = torch.empty((T, H), device="cuda")
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    q8.q8_embedding(eq, s, dev(ids), out_i8, err_flag=flag)
+    q8.q8_embedding(eq, s, dev(ids), out_f, err_flag=flag)
+    ref_i8, ref_f = O.embedding(eq_ref, s_ref, ids)
+    np.testing.assert_array_equal(host(out_i8), ref_i8)
+    assert_rel(host(out_f), ref_f)
+    assert host(flag)[0] == 0
+
+
+def test_embedding_bad_ids_flagged_and_zeroed(q8):
+    g = synth.rng(301)
+    V, H = 100, 64
+    eq = synth.random_int8(g, (V, H))
+    ids = np.array([3, V, 5, -1, 99], dtype=np.int32)
+    out = torch.full((5, H), 9.0, device="cuda")
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    q8.q8_embedding(dev(eq), scalar(10.0), dev(ids), out, err_flag=flag)
+    o = host(out)
+    assert host(flag)[0] == 1
+    assert not o[1].any() and not o[3].any()
+    good = np.array([0, 2, 4])
+    _, ref = O.embedding(eq, 10.0, ids[good])
+    assert_rel(o[good], ref)
+    with pytest.raises(O.OracleError):
+        O.embedding(eq, 10.0, ids)
+    # without a flag pointer the call still never reads out of range
+    q8.q8_embedding(dev(eq), scalar(10.0), dev(ids), out, err_flag=None)
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("H,T", [(768, 1000), (30, 33)])
+def test_embedding_sum3(q8, H, T):
+    g = synth.rng(302)
+    sizes = (2000, 512, 2)
+    tabs = [synth.weights(g, v, H) for v in sizes]
+    qs = [O.quantize_tensor(t) for t in tabs]
+    ids = [g.integers(0, v, size=T, dtype=np.int32) for v in sizes]
+    out = torch.empty((T, H), device="cuda")
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    scales = dev(np.array([s for _, s in qs], np.float32))
+    q8.q8_embedding_sum3(dev(qs[0][0]), dev(qs[1][0]), dev(qs[2][0]), scales, dev(ids[0]), dev(ids[1]), dev(ids[2]),
+                         out, err_flag=flag)
+    ref = O.embedding_sum3(qs[0][0], qs[0][1], qs[1][0], qs[1][1], qs[2][0], qs[2][1], *ids)
+    # three fp32 terms summed: absolute tolerance scaled by the largest term
+    mag = sum(np.abs(q[i].astype(np.float64)) / float(s) for (q, s), i in zip(qs, ids))
+    assert np.all(np.abs(host(out).astype(np.float64) - ref) <= 1e-6 * mag + 1e-12)
+    assert host(flag)[0] == 0
