@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized fully-connected hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of the BERT-Large encoder-layer
+workload (batch 32 x seq 384 = 12288 tokens, hidden 1024, FFN 4096):
+
+    int8 embedding gather (word + position + type, fp32 out)                 -- secondary path
+    for each FC of the layer (fused Q|K|V, attention-out, FFN1, FFN2):
+        abs-max of the fp32 input -> S_x = 127/max -> quantize -> int8 MFMA GEMM with fused
+        Int32 bias + dequantize (FFN1 also fuses GELU and the abs-max of its output, which
+        feeds FFN2's scale)
+
+All inputs are seeded synthetic tensors already resident in HBM when the timed region starts.
+The fp32 glue between the FCs (attention, LayerNorm) is not part of the hot path: it is run
+once, untimed, with PyTorch ops to give every FC an input of realistic distribution.
+
+Prints ONE JSON line.  value = int8 tera-ops/s of the six FC GEMMs (2*M*N*K each) over the
+whole step time (quantize passes and embedding included).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "int8 TOPS + % MFMA peak on BERT FC GEMMs; tokens/s per quantized BERT layer"
+INT8_PEAK_TOPS = 5033.0      # MI355X published dense int8 matrix peak
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--seq", type=int, default=384)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=768)
+    return ap.parse_args()
+
+
+class Layer:
+    """Device-resident quantized weights of one encoder layer plus work buffers."""
+
+    def __init__(self, q8, torch, d, vocab_tables, ids):
+        self.q8, self.torch = q8, torch
+        dev = "cuda"
+        self.batch, self.seq = d["batch"], d["seq"]
+        self.M = d["batch"] * d["seq"]
+        self.H, self.F, self.heads = d["hidden"], d["ffn"], d["heads"]
+        M, H, F = self.M, self.H, self.F
+
+        def up(a):
+            return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+        def quant_weight(W):
+            wd = up(W)
+            a = torch.zeros(1, device=dev)
+            s = torch.zeros(1, device=dev)
+            q8.q8_absmax(wd, a, s)
+            wq = torch.empty(W.shape, dtype=torch.int8, device=dev)
+            q8.q8_quantize(wd, s, wq)
+            return wq, s
+
+        parts = [quant_weight(d["W" + n]) for n in ("q", "k", "v")]
+        self.w_qkv = torch.cat([p[0] for p in parts], 0).contiguous()
+        self.s_qkv = torch.cat([p[1] for p in parts]).contiguous()
+        self.b_qkv = up(np.concatenate([d["bq"], d["bk"], d["bv"]]))
+        self.w_o, self.s_o = quant_weight(d["Wo"])
+        self.b_o = up(d["bo"])
+        self.w_1, self.s_1 = quant_weight(d["W1"])
+        self.b_1 = up(d["b1"])
+        self.w_2, self.s_2 = quant_weight(d["W2"])
+        self.b_2 = up(d["b2"])
+        # embedding tables (int8) and ids
+        tabs = [quant_weight(vocab_tables[k]) for k in ("word", "position", "token_type")]
+        self.tables = [t[0] for t in tabs]
+        self.table_scales = torch.cat([t[1] for t in tabs]).contiguous()
+        self.ids = [up(ids[k]) for k in ("word", "position", "token_type")]
+        self.emb = torch.empty((M, H), device=dev)
+        self.err = torch.zeros(1, dtype=torch.int32, device=dev)
+        # activations and work buffers
+        self.x = up(d["x"])
+        self.ctx = torch.empty((M, H), device=dev)
+        self.h1 = torch.empty((M, H), device=dev)
+        self.qkv = torch.empty((M, 3 * H), device=dev)
+        self.attn_out = torch.empty((M, H), device=dev)
+        self.g = torch.empty((M, F), device=dev)
+        self.out = torch.empty((M, H), device=dev)
+        self.xq = torch.empty(M * F, dtype=torch.int8, device=dev)
+        self.scal = torch.zeros(8, device=dev)       # [amax, scale] pairs + fused abs-max slot
+        self.gemm_ops = 2.0 * M * (3 * H * H + H * H + 2 * H * F)
+        self.events = None
+
+    def _fc_dyn(self, x, K, wq, sw, b, y, n_groups=1, flags=0, out_amax=None):
+        q8 = self.q8
+        M = self.M
+        amax, sx = self.scal[0:1], self.scal[1:2]
+        xq = self.xq[: M * K].view(M, K)
+        q8.q8_absmax(x, amax, sx)
+        q8.q8_quantize(x, sx, xq)
+        q8.q8_linear(xq, wq, b, sx, sw, y, n_groups=n_groups, out_amax=out_amax, flags=flags)
+
+    def step(self, ev=None):
+        """The timed hot path.  ev: optional (start, end) event pair recorded around FFN2's GEMM."""
+        q8, torch = self.q8, self.torch
+        M, H, F = self.M, self.H, self.F
+        q8.q8_embedding_sum3(self.tables[0], self.tables[1], self.tables[2], self.table_scales, self.ids[0],
+                             self.ids[1], self.ids[2], self.emb, err_flag=self.err)
+        self._fc_dyn(self.x, H, self.w_qkv, self.s_qkv, self.b_qkv, self.qkv, n_groups=3)
+        self._fc_dyn(self.ctx, H, self.w_o, self.s_o, self.b_o, self.attn_out)
+        # FFN1: GELU and the abs-max of the GELU output come out of the GEMM epilogue
+        g_amax, g_scale = self.scal[4:5], self.scal[5:6]
+        g_amax.zero_()
+        self._fc_dyn(self.h1, H, self.w_1, self.s_1, self.b_1, self.g, flags=q8.EPI_GELU | q8.EPI_ABSMAX,
+                     out_amax=g_amax)
+        # FFN2: scale from the fused abs-max, one quantize pass, GEMM
+        xq = self.xq[: M * F].view(M, F)
+        q8.q8_scale_from_amax(g_amax, g_scale)
+        q8.q8_quantize(self.g, g_scale, xq)
+        if ev is not None:
+            ev[0].record()
+        q8.q8_linear(xq, self.w_2, self.b_2, g_scale, self.s_2, self.out)
+        if ev is not None:
+            ev[1].record()
+
+    def glue_once(self):
+        """Untimed fp32 glue (attention, residual, LayerNorm) so every FC sees realistic inputs."""
+        torch = self.torch
+        F_ = torch.nn.functional
+        M, H = self.M, self.H
+        self._fc_dyn(self.x, H, self.w_qkv, self.s_qkv, self.b_qkv, self.qkv, n_groups=3)
+        B, S = self.batch, self.seq
+        hd = H // self.heads
+        q, k, v = (t.reshape(B, S, self.heads, hd).transpose(1, 2) for t in self.qkv.split(H, dim=1))
+        ctx = F_.scaled_dot_product_attention(q, k, v)
+        self.ctx.copy_(ctx.transpose(1, 2).reshape(M, H))
+        self._fc_dyn(self.ctx, H, self.w_o, self.s_o, self.b_o, self.attn_out)
+        self.h1.copy_(F_.layer_norm(self.x + self.attn_out, (H,), eps=1e-12))
+        torch.cuda.synchronize()
+
+
+def cpu_baseline(d, sample_tokens):
+    """The CPU oracle, as it stands, on the first `sample_tokens` tokens of the same workload."""
+    from oracle import q8_oracle as O
+    threads = min(os.cpu_count() or 1, 16)
+    M = sample_tokens
+    x = d["x"][:M]
+    g = np.random.default_rng(99)
+    ctx = g.standard_normal((M, d["hidden"]), dtype=np.float32)
+    h1 = g.standard_normal((M, d["hidden"]), dtype=np.float32)
+    ws = {n: O.quantize_tensor(d["W" + n]) for n in ("q", "k", "v", "o", "1", "2")}   # offline, untimed
+    t0 = time.perf_counter()
+    for n in ("q", "k", "v"):
+        O.linear(x, ws[n][0], ws[n][1], d["b" + n], threads=threads)
+    O.linear(ctx, ws["o"][0], ws["o"][1], d["bo"], threads=threads)
+    f1 = O.linear(h1, ws["1"][0], ws["1"][1], d["b1"], act_gelu=True, threads=threads)
+    O.linear(f1["y"], ws["2"][0], ws["2"][1], d["b2"], threads=threads)
+    dt = time.perf_counter() - t0
+    H, F = d["hidden"], d["ffn"]
+    ops = 2.0 * M * (4 * H * H + 2 * H * F)
+    return dict(value=ops / dt / 1e12, unit="int8 TOPS", cores=threads, kind="oracle",
+                sample=f"all six FC layers (abs-max, quantize, int8 GEMM, dequantize, GELU) of the same layer on the "
+                       f"first {M} of {d['batch'] * d['seq']} tokens; {dt:.2f} s wall",
+                tokens_per_s=M / dt)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU; run with --gpus 1 (no multi-GPU path exists)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    from paper_1910_06188_amd import q8, synth
+
+    d = synth.bert_large_layer(seed=3, batch=args.batch, seq=args.seq)
+    tables = synth.embedding_tables(seed=5, hidden=d["hidden"])
+    ids = synth.token_ids(seed=6, batch=args.batch, seq=args.seq)
+    layer = Layer(q8, torch, d, tables, ids)
+    layer.glue_once()
+
+    for _ in range(args.warmup):
+        layer.step()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        layer.step(evs[i])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert int(layer.err.item()) == 0
+
+    ms_per_step = dt / args.steps * 1e3
+    tops = layer.gemm_ops / (dt / args.steps) / 1e12
+    tokens_per_s = layer.M / (dt / args.steps)
+    # dominant kernel: the FFN2 GEMM (12288 x 1024 x 4096), timed with events on the launch stream
+    ffn2_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+    ffn2_ops = 2.0 * layer.M * layer.H * layer.F
+    ffn2_tops = ffn2_ops / (ffn2_ms * 1e-3) / 1e12
+    out = {
+        "metric": METRIC, "value": round(tops, 2), "unit": "int8 TOPS", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "i8", "data": "synthetic",
+        "config": {"workload": "BERT-Large encoder layer, batch %d x seq %d (BASELINE configs[3]): six quantized FC "
+                               "layers (fused QKV, attn-out, FFN1+GELU, FFN2) with dynamic per-tensor scales, plus "
+                               "the int8 3-table embedding gather" % (args.batch, args.seq),
+                   "tokens": layer.M, "hidden": layer.H, "ffn": layer.F, "fp32_glue_timed": False},
+        "tokens_per_s": round(tokens_per_s, 1),
+        "pct_int8_mfma_peak_whole_step": round(100.0 * tops / INT8_PEAK_TOPS, 2),
+        "roofline": {"bound": "mfma", "kernel": "gemm_mfma_kernel (FFN2 12288x1024x4096, fp32 out)",
+                     "achieved": round(ffn2_tops, 1), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
+                     "frac": round(ffn2_tops / INT8_PEAK_TOPS, 4), "avg_launch_us": round(ffn2_ms * 1e3, 2),
+                     "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(d, args.cpu_sample_tokens)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -6,13 +6,12 @@
 // Both operands are K-contiguous ("NT" GEMM), so a 16-byte vector of either one is
 // 16 consecutive k of one row -- exactly one lane's share of an i8 MFMA operand.
 //
-// MFMA kernel: a workgroup owns a BM x BN tile of y and walks K in steps of 128 bytes.
-// Operand tiles go HBM/L2 -> LDS directly (buffer_load ... lds, 16 B per lane), double
-// buffered; waves read 16-byte fragments back (ds_read_b128) and issue
-// v_mfma_i32_32x32x32_i8.  LDS rows are 128 B (8 chunks of 16 B); chunk c of row r is
-// kept at slot c ^ ((r ^ (r >> 3)) & 7), which spreads the 32 rows a fragment read
-// touches over all banks.  The swizzle costs nothing on the way in because each lane of
-// a direct-to-LDS load picks its own global address while the LDS side stays linear.
+// MFMA kernel: a workgroup owns a BM x BN tile of y and walks K in stages of 64 bytes.
+// Operand tiles go HBM/L2 -> LDS directly (buffer_load ... lds, 16 B per lane) into a
+// ring of stage buffers; waves read 16-byte fragments back (ds_read_b128) and issue
+// v_mfma_i32_32x32x32_i8.  LDS rows are swizzled so fragment reads are free of bank
+// conflicts; the swizzle costs nothing on the way in because each lane of a
+// direct-to-LDS load picks its own global address while the LDS side stays linear.
 #include <type_traits>
 
 #include "q8_device.h"
@@ -20,7 +19,9 @@
 
 namespace q8 {
 
-constexpr int kBK = 128;  // bytes (= int8 elements) of K per LDS row and per pipeline stage
+constexpr int kBK = 128;  // bytes (= int8 elements) of K per LDS row and per pipeline stage: one full
+                          // 128-byte cache line of every operand row, so no line is fetched twice
+constexpr int kKS = kBK / 32;  // 32-byte MFMA k-steps per stage
 
 __device__ __forceinline__ unsigned f32_abs_bits(float v) { return __float_as_uint(v) & 0x7fffffffu; }
 
@@ -52,7 +53,29 @@ __device__ __forceinline__ unsigned epilogue_store(const Epilogue& ep, int64_t i
     return f32_abs_bits(y);
 }
 
+// LDS rows are kBK = 128 bytes (8 chunks of 16 B).  Chunk c of row r is kept at slot
+// c ^ ((r ^ (r >> 3)) & 7): the 16 rows a ds_read_b128 serves per cycle then cover all 64
+// banks (measured conflict-free on gfx950; r & 7 alone leaves a 2-way conflict).
 __device__ __forceinline__ int swizzle_of_row(int r) { return (r ^ (r >> 3)) & 7; }
+
+// s_waitcnt immediates for gfx9: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8.
+__host__ __device__ constexpr int waitcnt_vm(int vm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4) | (15 << 8); }
+__host__ __device__ constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4); }
+
+// Scheduling recipe for one k-step: the LDS reads and global loads are spread evenly
+// behind the MFMAs, so each memory operation issues in the shadow of a running MFMA.
+template <int MFMAS, int DSREADS, int VMEMS, int I = 0>
+__device__ __forceinline__ void interleave()
+{
+    if constexpr (I < MFMAS) {
+        constexpr int ds = (DSREADS * (I + 1)) / MFMAS - (DSREADS * I) / MFMAS;
+        constexpr int vm = (VMEMS * (I + 1)) / MFMAS - (VMEMS * I) / MFMAS;
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);               // one MFMA
+        if constexpr (ds > 0) __builtin_amdgcn_sched_group_barrier(0x100, ds, 0);  // LDS reads
+        if constexpr (vm > 0) __builtin_amdgcn_sched_group_barrier(0x020, vm, 0);  // global loads
+        interleave<MFMAS, DSREADS, VMEMS, I + 1>();
+    }
+}
 
 // Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous run of
 // tile ids so that the tiles sharing operand rows meet in the same L2.
@@ -63,7 +86,31 @@ __device__ __forceinline__ int xcd_remap(int b, int g)
     return xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
 }
 
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef __attribute__((address_space(3))) char* lds_ptr_t;
+
+// Raw buffer descriptor (gfx9 layout): 48-bit base, stride 0, num_records in bytes.
+__device__ __forceinline__ v4i make_rsrc(const void* base, unsigned bytes)
+{
+    const unsigned long long p = reinterpret_cast<unsigned long long>(base);
+    v4i r;
+    r[0] = (int)(unsigned)(p & 0xffffffffu);
+    r[1] = (int)(unsigned)((p >> 32) & 0xffffu);
+    r[2] = (int)bytes;
+    r[3] = 0x00020000;
+    return r;
+}
+
+// 16 bytes per lane from a buffer straight into LDS: lane l lands at lds_addr + 16*l.
+// rsrc, soff and lds_addr are wave-uniform.  Written as asm so that the compiler does not
+// pair every later LDS read with a full vmcnt(0) wait; the kernel orders these loads
+// against its LDS reads itself (s_waitcnt vmcnt + barrier).
+__device__ __forceinline__ void lds_dma16(v4i rsrc, unsigned voff, unsigned soff, unsigned lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+                 : "memory");
+}
 
 // Compile-time loop: the body sees its index as a constant, so accumulator registers
 // are always addressed statically.
@@ -76,9 +123,26 @@ __device__ __forceinline__ void static_for(F&& f)
     }
 }
 
+// Software-pipelined MFMA kernel.
+//
+// K is walked in stages of kBK = 128 bytes.  The LDS holds STAGES stage buffers in a ring.
+// A stage is four 32-byte k-steps; the fragments of the next k-step are read from LDS
+// while the MFMAs of the current one run, so that the matrix pipe never waits for an LDS
+// round trip, and the barrier sits before the last k-step, whose fragments are already in
+// registers, so the stage buffer can be refilled a whole stage ahead of its use:
+//
+//   k-steps 0..2 of stage t : ds_read fragments of the next k-step     || MFMAs
+//   wait: own reads of stage t done, own loads of stage t+1 landed;  barrier
+//   k-step 3 of stage t     : buffer_load stage t+STAGES -> ring slot of stage t,
+//                             ds_read fragments (t+1, k-step 0)         || MFMAs
+//
+// Loads past the end of K go through an empty buffer descriptor (num_records = 0): the
+// hardware drops them and returns zeros, so the vmcnt bookkeeping is the same in every
+// trip and no memory is touched.
+//
 // kPlain: fp32 output with no optional epilogue stage and no accumulator dump -- the
 // common case gets a kernel of its own so the optional stages cost it nothing.
-template <int BM, int BN, int WGM, int WGN, bool kPlain>
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool kPlain>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const int8_t* __restrict__ X,
                                                                    const int8_t* __restrict__ W, int M, int N, int K,
                                                                    int tiles_n, int group_m, Epilogue ep)
@@ -89,13 +153,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const int8_t* 
     constexpr int FM = TM / 32, FN = TN / 32;    // 32x32 MFMA blocks per wave tile
     constexpr int A_BYTES = BM * kBK, B_BYTES = BN * kBK, STAGE = A_BYTES + B_BYTES;
     constexpr int A_LOADS = BM / 8 / NW, B_LOADS = BN / 8 / NW;  // 1 KiB wave loads per stage
+    constexpr int LOADS = A_LOADS + B_LOADS;
     static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must split over the waves");
     static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be made of 32x32 blocks");
+    static_assert(STAGES >= 2 && (STAGES - 1) * LOADS <= 63, "vmcnt is a 6-bit counter");
+    static_assert(STAGES * STAGE <= 160 * 1024, "LDS is 160 KiB per compute unit");
 
-    __shared__ __attribute__((aligned(1024))) char lds[2 * STAGE];
+    __shared__ __attribute__((aligned(1024))) char lds[STAGES * STAGE];
 
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned lds_base = (unsigned)(size_t)(lds_ptr_t)lds;
 
     // tile id -> (tm, tn): panels of group_m tile rows, column-major inside a panel
     int pid = xcd_remap(blockIdx.x, gridDim.x);
@@ -110,12 +178,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const int8_t* 
     const int m0 = (pid / tiles_n) * BM;
     const int n0 = (pid % tiles_n) * BN;
 
-    const __amdgpu_buffer_rsrc_t rsrc_a =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t*>(X), 0, (int)((unsigned)M * (unsigned)K), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsrc_b =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t*>(W), 0, (int)((unsigned)N * (unsigned)K), 0x00020000);
+    const unsigned bytes_a = (unsigned)M * (unsigned)K, bytes_b = (unsigned)N * (unsigned)K;
 
-    // Per-lane global byte offsets of this lane's chunk in each wave load (k-step 0).
+    // Per-lane global byte offsets of this lane's chunk in each wave load (k = 0).  One
+    // wave load covers 8 rows x 128 B; lane l fills row l/8, slot l%8 of the LDS side.
     // Rows beyond the matrix edge re-read the last row; their products are never stored.
     unsigned a_off[A_LOADS], b_off[B_LOADS];
 #pragma unroll
@@ -131,35 +197,37 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const int8_t* 
         b_off[i] = (unsigned)min(n0 + r, N - 1) * (unsigned)K + (unsigned)(c * 16);
     }
 
-    auto issue_loads = [&](int kt, int stage) {
-        char* base = lds + stage * STAGE;
-        const int koff = kt * kBK;
+    const int KT = K / kBK;
+    auto issue_loads = [&](int kt) {
+        const unsigned base = lds_base + (unsigned)((kt % STAGES) * STAGE);
+        const bool live = kt < KT;  // past the end of K: empty descriptor, nothing is fetched
+        const v4i ra = make_rsrc(X, live ? bytes_a : 0u);
+        const v4i rb = make_rsrc(W, live ? bytes_b : 0u);
+        const unsigned koff = live ? (unsigned)(kt * kBK) : 0u;
 #pragma unroll
-        for (int i = 0; i < A_LOADS; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lds_ptr_t)(base + (wave * A_LOADS + i) * 1024), 16,
-                                                     a_off[i], koff, 0, 0);
+        for (int i = 0; i < A_LOADS; ++i) lds_dma16(ra, a_off[i], koff, base + (wave * A_LOADS + i) * 1024);
 #pragma unroll
         for (int i = 0; i < B_LOADS; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_ptr_t)(base + A_BYTES + (wave * B_LOADS + i) * 1024),
-                                                     16, b_off[i], koff, 0, 0);
+            lds_dma16(rb, b_off[i], koff, base + A_BYTES + (wave * B_LOADS + i) * 1024);
     };
 
     // Fragment addressing: lane l of a 32x32x32 MFMA supplies row (l % 32) and the
     // 16 k-bytes numbered (l / 32) of a 32-byte k-step, for both operands.
     const int wm = wave / WGN, wn = wave % WGN;
     const int l32 = lane & 31, hi = lane >> 5;
-    int a_row_off[FM], a_swz[FM], b_row_off[FN], b_swz[FN];
+    int a_frag_off[FM][kKS], b_frag_off[FN][kKS];  // [block][k-step] byte offset inside a stage
 #pragma unroll
     for (int f = 0; f < FM; ++f) {
         int r = wm * TM + f * 32 + l32;
-        a_row_off[f] = r * kBK;
-        a_swz[f] = swizzle_of_row(r);
+#pragma unroll
+        for (int ks = 0; ks < kKS; ++ks) a_frag_off[f][ks] = r * kBK + (((ks * 2 + hi) ^ swizzle_of_row(r)) << 4);
     }
 #pragma unroll
     for (int f = 0; f < FN; ++f) {
         int r = wn * TN + f * 32 + l32;
-        b_row_off[f] = A_BYTES + r * kBK;
-        b_swz[f] = swizzle_of_row(r);
+#pragma unroll
+        for (int ks = 0; ks < kKS; ++ks)
+            b_frag_off[f][ks] = A_BYTES + r * kBK + (((ks * 2 + hi) ^ swizzle_of_row(r)) << 4);
     }
 
     v16i acc[FM][FN];
@@ -170,30 +238,49 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const int8_t* 
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
 
-    const int KT = K / kBK;
-    issue_loads(0, 0);
+    v4i fa[2][FM], fb[2][FN];  // fragments of the current / next k-step, double buffered in registers
+    auto read_frags = [&](int kt, int ks, v4i* a, v4i* b) {
+        const char* base = lds + (kt % STAGES) * STAGE;
+#pragma unroll
+        for (int f = 0; f < FM; ++f) a[f] = *reinterpret_cast<const v4i*>(base + a_frag_off[f][ks]);
+#pragma unroll
+        for (int f = 0; f < FN; ++f) b[f] = *reinterpret_cast<const v4i*>(base + b_frag_off[f][ks]);
+    };
+    auto mfma_step = [&](const v4i* a, const v4i* b) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
+    };
+
+#pragma unroll
+    for (int s = 0; s < STAGES; ++s) issue_loads(s);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm((STAGES - 1) * LOADS));  // stage 0 landed
+    __syncthreads();
+    read_frags(0, 0, fa[0], fb[0]);
+
     for (int kt = 0; kt < KT; ++kt) {
-        // this wave's share of stage kt has landed; after the barrier everyone's has, and
-        // every wave is done reading the other stage, which the next loads overwrite
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (kt + 1 < KT) issue_loads(kt + 1, (kt + 1) & 1);
-        const char* base = lds + (kt & 1) * STAGE;
+        // all k-steps but the last: next fragments in flight while the matrix pipe works
 #pragma unroll
-        for (int ks = 0; ks < kBK / 32; ++ks) {
-            v4i a[FM], b[FN];
-#pragma unroll
-            for (int f = 0; f < FM; ++f)
-                a[f] = *reinterpret_cast<const v4i*>(base + a_row_off[f] + (((ks * 2 + hi) ^ a_swz[f]) << 4));
-#pragma unroll
-            for (int f = 0; f < FN; ++f)
-                b[f] = *reinterpret_cast<const v4i*>(base + b_row_off[f] + (((ks * 2 + hi) ^ b_swz[f]) << 4));
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
+        for (int ks = 0; ks < kKS - 1; ++ks) {
+            read_frags(kt, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
+            mfma_step(fa[ks & 1], fb[ks & 1]);
+            interleave<FM * FN, FM + FN, 0>();
+            __builtin_amdgcn_sched_barrier(0);
         }
+        // own LDS reads of stage kt are complete and own loads of stage kt+1 have landed
+        // (the STAGES-2 younger stages may still be in flight)
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((STAGES - 2) * LOADS));
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        // last k-step: every wave has left stage kt's ring slot -- refill it with stage
+        // kt+STAGES -- and fetch the first fragments of stage kt+1
+        issue_loads(kt + STAGES);
+        read_frags(kt + 1, 0, fa[0], fb[0]);
+        mfma_step(fa[(kKS - 1) & 1], fb[(kKS - 1) & 1]);
+        interleave<FM * FN, FM + FN, 0>();
+        __builtin_amdgcn_sched_barrier(0);
     }
 
     // Epilogue.  Accumulator register e of lane l is row 8*(e/4) + 4*(l/32) + e%4 and
@@ -278,17 +365,17 @@ bool gemm_mfma_eligible(const int8_t* xq, const int8_t* wq, int64_t M, int64_t N
     return M > 0 && N > 0;
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, int STAGES>
 static int launch_tile(const int8_t* xq, const int8_t* wq, int M, int N, int K, int group_m, const Epilogue& ep,
                        hipStream_t st)
 {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const dim3 grid(tiles_m * tiles_n), block(WGM * WGN * 64);
     if (ep.flags == 0u && ep.acc_out == nullptr)
-        hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WGM, WGN, true>), grid, block, 0, st, xq, wq, M, N, K, tiles_n,
+        hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WGM, WGN, STAGES, true>), grid, block, 0, st, xq, wq, M, N, K, tiles_n,
                            group_m, ep);
     else
-        hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WGM, WGN, false>), grid, block, 0, st, xq, wq, M, N, K, tiles_n,
+        hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WGM, WGN, STAGES, false>), grid, block, 0, st, xq, wq, M, N, K, tiles_n,
                            group_m, ep);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
@@ -299,16 +386,27 @@ int launch_gemm_mfma(const int8_t* xq, const int8_t* wq, int64_t M64, int64_t N6
     const int M = (int)M64, N = (int)N64, K = (int)K64;
     int v = g_variant;
     if (v == 0) {
-        // large tiles once there is enough work to fill 256 compute units with them
-        const int64_t t256 = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
-        v = t256 >= 256 ? 1 : 3;
+        // Pick the tile whose launch leaves the 256 compute units least idle: large tiles
+        // once they fill the chip, else the 192-row tile if it divides the work evenly,
+        // else small tiles.
+        auto tiles = [&](int bm, int bn) { return (int64_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
+        auto idle = [&](int64_t t) { return (double)(((t + 255) / 256) * 256 - t) / (double)(((t + 255) / 256) * 256); };
+        const int64_t t256 = tiles(256, 256), t192 = tiles(192, 256);
+        if (t256 >= 256 && idle(t256) <= 0.10)
+            v = 2;
+        else if (t192 >= 192 && idle(t192) <= idle(t256))
+            v = 4;
+        else if (t256 >= 512)
+            v = 2;
+        else
+            v = 3;
     }
     const int group_m = 8;
     switch (v) {
-        case 1: return launch_tile<256, 256, 2, 2>(xq, wq, M, N, K, group_m, ep, st);
-        case 2: return launch_tile<256, 256, 2, 4>(xq, wq, M, N, K, group_m, ep, st);
-        case 3: return launch_tile<128, 128, 2, 2>(xq, wq, M, N, K, group_m, ep, st);
-        case 4: return launch_tile<256, 128, 2, 2>(xq, wq, M, N, K, group_m, ep, st);
+        case 1: return launch_tile<256, 256, 2, 2, 2>(xq, wq, M, N, K, group_m, ep, st);
+        case 2: return launch_tile<256, 256, 2, 4, 2>(xq, wq, M, N, K, group_m, ep, st);
+        case 3: return launch_tile<128, 128, 2, 2, 4>(xq, wq, M, N, K, group_m, ep, st);
+        case 4: return launch_tile<192, 256, 2, 2, 2>(xq, wq, M, N, K, group_m, ep, st);
         default: return 1;
     }
 }

@@ -1,0 +1,121 @@
+"""Parity at the benchmark's full shapes (BERT-Large encoder layer, 12288 tokens), in the
+launch configuration bench.py times (automatic tile choice).  The quantize stage is compared
+in full; GEMM outputs are compared on sampled rows that the oracle computes one by one
+(every 256-row tile band is hit, plus the first and last rows)."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from oracle import q8_oracle as O  # noqa: E402
+from paper_1910_06188_amd import synth  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def q8():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1910_06188_amd import q8 as mod
+    return mod
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def one():
+    return torch.zeros(1, device="cuda")
+
+
+@pytest.mark.parametrize("M,K,N,gelu", [(12288, 1024, 4096, True), (12288, 4096, 1024, False),
+                                        (12288, 1024, 3072, False), (4096, 768, 3072, False),
+                                        (4096, 3072, 768, False), (8192, 768, 2304, False)])
+def test_fullsize_fc_sampled_rows(q8, M, K, N, gelu):
+    g = synth.rng(7000 + N)
+    x = synth.activations(g, M, K)
+    n_groups = 3 if N in (3072, 2304) and K in (1024, 768) and not gelu else 1
+    Ws = [synth.weights(g, N // n_groups, K) * np.float32(1.0 + 0.5 * i) for i in range(n_groups)]
+    b = synth.bias(g, N)
+    # weights offline on the GPU, checked against the oracle in full
+    wqs, sws = [], []
+    for W in Ws:
+        wd = dev(W)
+        a, s = one(), one()
+        q8.q8_absmax(wd, a, s)
+        wq = torch.empty(W.shape, dtype=torch.int8, device="cuda")
+        q8.q8_quantize(wd, s, wq)
+        wq_ref, s_ref = O.quantize_tensor(W)
+        assert s.item() == float(s_ref)
+        np.testing.assert_array_equal(wq.cpu().numpy(), wq_ref)
+        wqs.append(wq)
+        sws.append(s)
+    wq = torch.cat(wqs, 0).contiguous()
+    sw = torch.cat(sws).contiguous()
+    # activations: abs-max, scale and every int8 code against the oracle
+    xd = dev(x)
+    a, sx = one(), one()
+    q8.q8_absmax(xd, a, sx)
+    xq = torch.empty((M, K), dtype=torch.int8, device="cuda")
+    q8.q8_quantize(xd, sx, xq)
+    sx_ref = O.scale(O.absmax(x))
+    assert a.item() == float(O.absmax(x)) and sx.item() == float(sx_ref)
+    xq_ref = O.quantize(x, sx_ref)
+    np.testing.assert_array_equal(xq.cpu().numpy(), xq_ref)
+    # GEMM + epilogue
+    y = torch.empty((M, N), device="cuda")
+    acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    amax = one()
+    flags = (q8.EPI_GELU | q8.EPI_ABSMAX) if gelu else 0
+    q8.q8_linear(xq, wq, dev(b), sx, sw, y, n_groups=n_groups, acc_out=acc, out_amax=amax if gelu else None,
+                 flags=flags)
+    y_plain = None
+    if not gelu:
+        y_plain = torch.empty((M, N), device="cuda")
+        q8.q8_linear(xq, wq, dev(b), sx, sw, y_plain, n_groups=n_groups)      # the kernel bench.py times
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, 1, M - 1, M - 2], np.arange(0, M, 256) + 37, np.arange(255, M, 512),
+                                     g.integers(0, M, size=24)]))
+    rows = rows[rows < M]
+    swh = sw.cpu().numpy()
+    bq = O.quantize_bias(b, N, sx_ref, swh)
+    acc_ref = O.gemm_i8(xq_ref[rows], wq.cpu().numpy(), bq, threads=8)
+    np.testing.assert_array_equal(acc.cpu().numpy()[rows], acc_ref)
+    y_ref = O.dequant(acc_ref, sx_ref, swh)
+    yh = y.cpu().numpy()
+    if gelu:
+        gl = O.gelu(y_ref).astype(np.float64)
+        assert np.all(np.abs(yh[rows].astype(np.float64) - gl) <= 1e-6 + 1e-5 * np.abs(gl))
+        assert amax.item() == np.abs(yh).max()
+    else:
+        ref64 = y_ref.astype(np.float64)
+        assert np.all(np.abs(yh[rows].astype(np.float64) - ref64) <= 1e-6 * np.abs(ref64))
+        assert np.all(np.abs(y_plain.cpu().numpy()[rows].astype(np.float64) - ref64) <= 1e-6 * np.abs(ref64))
+        # the two kernels (with and without the accumulator dump) agree everywhere
+        assert torch.equal(y, y_plain)
+    # property that holds at any size: every accumulator is consistent with its dequantised value
+    accf = acc.cpu().numpy().astype(np.float64)
+    if not gelu:
+        per = N // n_groups
+        scale = np.repeat(float(sx_ref) * swh.astype(np.float64), per)[None, :]
+        assert np.all(np.abs(yh.astype(np.float64) * scale - accf) <= 1e-6 * np.abs(accf) + 1e-9)
+
+
+def test_fullsize_embedding_bert_base_tables(q8):
+    tabs = synth.embedding_tables(seed=5, hidden=768)
+    ids = synth.token_ids(seed=6, batch=64, seq=128)
+    qs = {k: O.quantize_tensor(v) for k, v in tabs.items()}
+    order = ("word", "position", "token_type")
+    out = torch.empty((64 * 128, 768), device="cuda")
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    scales = dev(np.array([qs[k][1] for k in order], np.float32))
+    q8.q8_embedding_sum3(*[dev(qs[k][0]) for k in order], scales, *[dev(ids[k]) for k in order], out, err_flag=flag)
+    ref = O.embedding_sum3(qs["word"][0], qs["word"][1], qs["position"][0], qs["position"][1],
+                           qs["token_type"][0], qs["token_type"][1], ids["word"], ids["position"], ids["token_type"])
+    mag = sum(np.abs(qs[k][0][ids[k]].astype(np.float64)) / float(qs[k][1]) for k in order)
+    assert np.all(np.abs(out.cpu().numpy().astype(np.float64) - ref) <= 1e-6 * mag + 1e-12)
+    assert flag.item() == 0
+    # single-table int8 gather, full word table
+    o8 = torch.empty((64 * 128, 768), dtype=torch.int8, device="cuda")
+    q8.q8_embedding(dev(qs["word"][0]), scales[0:1], dev(ids["word"]), o8)
+    np.testing.assert_array_equal(o8.cpu().numpy(), qs["word"][0][ids["word"]])
