@@ -44,6 +44,9 @@ typedef enum {
  * -128 included, can overflow the int32 accumulator before the bias is added. */
 #define Q8_MAX_K 131071
 
+/* Floats of scalar scratch q8_linear_f32 needs: abs-max, scale and up to 1024 partial maxima. */
+#define Q8_SCAL_WORK 1026
+
 /* q8_linear epilogue bits. */
 #define Q8_EPI_GELU 1u     /* y <- gelu(y), exact-erf form, in fp32 (GELU stays FP32: Section 3) */
 #define Q8_EPI_ABSMAX 2u   /* out_amax[0] <- max(out_amax[0], max|y|) over the fp32 outputs of this call */
@@ -77,6 +80,17 @@ q8_status q8_scale_from_amax(const float* amax, float* scale_out, void* stream);
 q8_status q8_quantize(const float* x, int64_t n, const float* scale, int8_t* q, void* stream);
 
 /*
+ * Eq. 3 then Eq. 1 in one launch: amax[0..n_amax) hold abs-max values whose maximum is the
+ * abs-max of the tensor being quantized (one value from q8_absmax or from the
+ * Q8_EPI_ABSMAX epilogue, or several partial maxima).  Computes a = max_i amax[i],
+ * S = 127 / a (1.0 if a is 0), writes scale_out[0] = S and, if amax_out is not NULL,
+ * amax_out[0] = a, and q[i] = Clamp(round(x[i] * S), -127, 127).
+ *   n >= 0; n_amax >= 1; amax_out and scale_out must not overlap amax[0..n_amax).
+ */
+q8_status q8_quantize_amax(const float* x, int64_t n, const float* amax, int n_amax, float* amax_out,
+                           float* scale_out, int8_t* q, void* stream);
+
+/*
  * The quantized FC layer at inference (Section 3): Int8 x Int8 GEMM accumulated in
  * Int32 onto the Int32 bias, then dequantized for the FP32 consumers.
  *     bq[n]    = Clamp(round(bias[n] * (sx * sw[g(n)])), -(2^31-1), 2^31-1)   (0 if bias is NULL)
@@ -88,7 +102,8 @@ q8_status q8_quantize(const float* x, int64_t n, const float* scale, int8_t* q, 
  *   paper's layer; 3 packs the Q, K and V projections, each keeping its own S_W.
  *   y: fp32[M,N], or int8[M,N] with Q8_EPI_REQUANT (then next_scale fp32[1] is required).
  *   acc_out: int32[M,N] or NULL -- dump of the post-bias accumulator, for parity checks.
- *   out_amax: fp32[1], required with Q8_EPI_ABSMAX; the caller sets it to 0 beforehand.
+ *   out_amax: fp32[1], required with Q8_EPI_ABSMAX; the caller sets it to 0 beforehand
+ *   (one atomic max per workgroup lands in it).
  *   Epilogue order: dequantize, GELU, abs-max, requantize.
  * M, N >= 0 (either 0: nothing is written); 0 <= K <= Q8_MAX_K; sizes are otherwise
  * free -- shapes with K % 128 == 0 and 16-byte aligned xq/wq take the MFMA kernel,
@@ -104,8 +119,9 @@ q8_status q8_linear(const int8_t* xq, const int8_t* wq, const float* bias,
 /*
  * Dynamic-quantization FC layer in one call (Section 4.1): abs-max of x, S_x = 127/max,
  * quantize, then q8_linear.  Same results as calling the three entry points in turn.
- *   x fp32[M,K]; xq_work int8[M*K] and scal_work fp32[2] are caller-provided scratch
- *   (on return scal_work[0] = max|x|, scal_work[1] = S_x, xq_work = the int8 codes).
+ *   x fp32[M,K]; xq_work int8[M*K] and scal_work fp32[Q8_SCAL_WORK] are caller-provided
+ *   scratch (on return scal_work[0] = max|x|, scal_work[1] = S_x, xq_work = the int8 codes;
+ *   the rest of scal_work holds per-workgroup partial maxima).
  *   Other arguments as q8_linear.
  */
 q8_status q8_linear_f32(const float* x, const int8_t* wq, const float* bias,

@@ -58,6 +58,19 @@ q8_status q8_quantize(const float* x, int64_t n, const float* scale, int8_t* q, 
     return q8::launch_quantize(x, n, scale, q, as_stream(stream)) ? Q8_ERR_LAUNCH : Q8_OK;
 }
 
+q8_status q8_quantize_amax(const float* x, int64_t n, const float* amax, int n_amax, float* amax_out,
+                           float* scale_out, int8_t* q, void* stream)
+{
+    if (n < 0 || n_amax < 1) return Q8_ERR_SHAPE;
+    if (!amax || !scale_out) return Q8_ERR_NULL;
+    if (n > 0 && (!x || !q)) return Q8_ERR_NULL;
+    if (misaligned(x, 4) || misaligned(amax, 4) || misaligned(amax_out, 4) || misaligned(scale_out, 4))
+        return Q8_ERR_ALIGN;
+    if (n == 0) return q8::launch_scale_from_amax(amax, scale_out, as_stream(stream)) ? Q8_ERR_LAUNCH : Q8_OK;
+    return q8::launch_quantize_amax(x, n, amax, n_amax, amax_out, scale_out, q, as_stream(stream)) ? Q8_ERR_LAUNCH
+                                                                                                    : Q8_OK;
+}
+
 q8_status q8_linear(const int8_t* xq, const int8_t* wq, const float* bias, const float* sx, const float* sw,
                     int n_groups, int64_t M, int64_t N, int64_t K, void* y, int32_t* acc_out, float* out_amax,
                     const float* next_scale, uint32_t flags, void* stream)
@@ -92,10 +105,17 @@ q8_status q8_linear_f32(const float* x, const int8_t* wq, const float* bias, con
     if (s != Q8_OK) return s;
     if (M > 0 && K > 0 && (!x || !xq_work)) return Q8_ERR_NULL;
     if (misaligned(x, 4)) return Q8_ERR_ALIGN;
-    s = q8_absmax(x, M * K, scal_work, scal_work + 1, stream);
-    if (s != Q8_OK) return s;
-    s = q8_quantize(x, M * K, scal_work + 1, xq_work, stream);
-    if (s != Q8_OK) return s;
+    if (M * K == 0) {
+        s = q8_absmax(x, 0, scal_work, scal_work + 1, stream);
+        if (s != Q8_OK) return s;
+    } else {
+        // abs-max slots in scal_work[2..], folded by the quantize kernel: no atomics, no extra launch
+        int slots = 0;
+        if (q8::launch_absmax_partial(x, M * K, scal_work + 2, &slots, as_stream(stream))) return Q8_ERR_LAUNCH;
+        if (q8::launch_quantize_amax(x, M * K, scal_work + 2, slots, scal_work, scal_work + 1, xq_work,
+                                     as_stream(stream)))
+            return Q8_ERR_LAUNCH;
+    }
     return q8_linear(xq_work, wq, bias, scal_work + 1, sw, n_groups, M, N, K, y, acc_out, out_amax, next_scale, flags,
                      stream);
 }

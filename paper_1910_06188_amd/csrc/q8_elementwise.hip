@@ -8,16 +8,13 @@ namespace q8 {
 
 constexpr int kEwThreads = 256;
 constexpr int kEwUnroll = 4;  // float4 loads in flight per thread per trip
+constexpr int kMaxEwGrid = 1024;  // also the number of abs-max slots the fused path may use
 
 // Order of non-negative binary32 values equals the order of their bit patterns,
 // so the reduction runs on integers and ends in one atomic max per workgroup.
 __device__ __forceinline__ unsigned abs_bits(float v) { return __float_as_uint(v) & 0x7fffffffu; }
 
-__global__ void absmax_init_kernel(unsigned* amax_bits, unsigned* ticket)
-{
-    amax_bits[0] = 0u;
-    if (ticket) ticket[0] = 0u;
-}
+__global__ void absmax_init_kernel(unsigned* amax_bits) { amax_bits[0] = 0u; }
 
 // Empty tensor: behaves as all zeros.
 __global__ void absmax_empty_kernel(float* amax, float* scale)
@@ -26,12 +23,9 @@ __global__ void absmax_empty_kernel(float* amax, float* scale)
     if (scale) scale[0] = 1.0f;
 }
 
-// x is walked as aligned float4 vectors; `head` leading and the trailing scalars
-// (fewer than 4 each) are taken by the first threads of block 0.
-// `ticket` aliases the scale output: it counts finished workgroups and the last one
-// overwrites it with S = 127 / amax, so scale and abs-max come out of one launch.
-__global__ __launch_bounds__(kEwThreads) void absmax_kernel(const float* __restrict__ x, int64_t n, int head,
-                                                             unsigned* amax_bits, unsigned* ticket)
+// Per-thread abs-max of this thread's share of x.  x is walked as aligned float4 vectors;
+// `head` leading and the trailing scalars (fewer than 4 each) are taken by block 0.
+__device__ __forceinline__ unsigned absmax_thread(const float* __restrict__ x, int64_t n, int head)
 {
     unsigned m = 0u;
     const float4* xv = reinterpret_cast<const float4*>(x + head);
@@ -59,7 +53,12 @@ __global__ __launch_bounds__(kEwThreads) void absmax_kernel(const float* __restr
         int64_t t = tail0 + threadIdx.x;
         if (t < n) m = max(m, abs_bits(x[t]));
     }
+    return m;
+}
 
+// Max over the workgroup; valid in thread 0.
+__device__ __forceinline__ unsigned block_max_u32(unsigned m)
+{
     __shared__ unsigned wave_part[kEwThreads / 64];
     m = wave_max_u32(m);
     if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = m;
@@ -67,16 +66,28 @@ __global__ __launch_bounds__(kEwThreads) void absmax_kernel(const float* __restr
     if (threadIdx.x == 0) {
 #pragma unroll
         for (int w = 1; w < kEwThreads / 64; ++w) m = max(m, wave_part[w]);
-        atomicMax(amax_bits, m);
-        if (ticket) {
-            __threadfence();
-            unsigned done = atomicAdd(ticket, 1u);
-            if (done == gridDim.x - 1) {
-                float amax = __uint_as_float(atomicMax(amax_bits, 0u));  // read at the coherence point
-                reinterpret_cast<float*>(ticket)[0] = scale_from_amax(amax);
-            }
-        }
     }
+    return m;
+}
+
+// Stand-alone abs-max: one atomic max per workgroup into a zeroed word.  No fences and
+// no "last block" ticket: device-scope fences cost an L2 write-back per workgroup on a
+// chip whose eight L2s are not coherent with each other, so the scale is left to a
+// follow-up launch (stream order makes the result visible).
+__global__ __launch_bounds__(kEwThreads) void absmax_atomic_kernel(const float* __restrict__ x, int64_t n, int head,
+                                                                    unsigned* amax_bits)
+{
+    unsigned m = block_max_u32(absmax_thread(x, n, head));
+    if (threadIdx.x == 0) atomicMax(amax_bits, m);
+}
+
+// Fused path: each workgroup leaves its abs-max in its own slot; the quantize kernel that
+// follows folds the slots.  No atomics at all.
+__global__ __launch_bounds__(kEwThreads) void absmax_partial_kernel(const float* __restrict__ x, int64_t n, int head,
+                                                                     unsigned* __restrict__ partials)
+{
+    unsigned m = block_max_u32(absmax_thread(x, n, head));
+    if (threadIdx.x == 0) partials[blockIdx.x] = m;
 }
 
 __global__ void scale_from_amax_kernel(const float* amax, float* scale) { scale[0] = scale_from_amax(amax[0]); }
@@ -116,6 +127,56 @@ __global__ __launch_bounds__(kEwThreads) void quantize_vec_kernel(const float* _
     }
 }
 
+// Scale from n_amax abs-max values (their maximum is the tensor's abs-max), Eq. 3; block 0
+// also publishes the abs-max and the scale for the GEMM that follows.
+__device__ __forceinline__ float scale_from_partials(const float* __restrict__ amax, int n_amax, float* amax_out,
+                                                     float* scale_out)
+{
+    __shared__ unsigned folded;
+    unsigned m = 0u;
+    for (int i = threadIdx.x; i < n_amax; i += kEwThreads) m = max(m, abs_bits(amax[i]));
+    m = block_max_u32(m);
+    if (threadIdx.x == 0) folded = m;
+    __syncthreads();
+    const float a = __uint_as_float(folded);
+    const float s = scale_from_amax(a);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        if (amax_out) amax_out[0] = a;
+        scale_out[0] = s;
+    }
+    return s;
+}
+
+template <bool kVec>
+__global__ __launch_bounds__(kEwThreads) void quantize_amax_kernel(const float* __restrict__ x, int64_t n,
+                                                                    const float* __restrict__ amax, int n_amax,
+                                                                    float* amax_out, float* scale_out,
+                                                                    int8_t* __restrict__ q)
+{
+    const float s = scale_from_partials(amax, n_amax, amax_out, scale_out);
+    const int64_t stride = (int64_t)gridDim.x * kEwThreads;
+    int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x;
+    if (kVec) {
+        const float4* xv = reinterpret_cast<const float4*>(x);
+        unsigned* qv = reinterpret_cast<unsigned*>(q);
+        const int64_t nvec = n >> 2;
+        for (; i + (kEwUnroll - 1) * stride < nvec; i += kEwUnroll * stride) {
+            float4 v[kEwUnroll];
+#pragma unroll
+            for (int u = 0; u < kEwUnroll; ++u) v[u] = xv[i + u * stride];
+#pragma unroll
+            for (int u = 0; u < kEwUnroll; ++u) qv[i + u * stride] = pack4(v[u], s);
+        }
+        for (; i < nvec; i += stride) qv[i] = pack4(xv[i], s);
+        if (blockIdx.x == 0) {
+            int64_t t = (nvec << 2) + threadIdx.x;
+            if (t < n) q[t] = (int8_t)quantize_code(x[t], s);
+        }
+    } else {
+        for (; i < n; i += stride) q[i] = (int8_t)quantize_code(x[i], s);
+    }
+}
+
 // Any alignment.
 __global__ __launch_bounds__(kEwThreads) void quantize_scalar_kernel(const float* __restrict__ x, int64_t n,
                                                                       const float* __restrict__ scale,
@@ -131,9 +192,15 @@ static int ew_grid(int64_t work_items)
 {
     int64_t per_block = (int64_t)kEwThreads * kEwUnroll;
     int64_t g = (work_items + per_block - 1) / per_block;
-    const int64_t cap = 256 * 8;  // 8 workgroups per compute unit
+    const int64_t cap = kMaxEwGrid;  // 4 workgroups per compute unit
     if (g < 1) g = 1;
     return (int)(g < cap ? g : cap);
+}
+
+static int head_of(const float* x, int64_t n)
+{
+    int head = (int)(((16 - (reinterpret_cast<uintptr_t>(x) & 15)) & 15) >> 2);
+    return head > n ? (int)n : head;
 }
 
 int launch_absmax(const float* x, int64_t n, float* amax_out, float* scale_out, hipStream_t st)
@@ -143,11 +210,33 @@ int launch_absmax(const float* x, int64_t n, float* amax_out, float* scale_out, 
         return hipGetLastError() == hipSuccess ? 0 : 1;
     }
     unsigned* bits = reinterpret_cast<unsigned*>(amax_out);
-    unsigned* ticket = reinterpret_cast<unsigned*>(scale_out);
-    int head = (int)(((16 - (reinterpret_cast<uintptr_t>(x) & 15)) & 15) >> 2);
-    if (head > n) head = (int)n;
-    hipLaunchKernelGGL(absmax_init_kernel, dim3(1), dim3(1), 0, st, bits, ticket);
-    hipLaunchKernelGGL(absmax_kernel, dim3(ew_grid((n - head) >> 2)), dim3(kEwThreads), 0, st, x, n, head, bits, ticket);
+    const int head = head_of(x, n);
+    hipLaunchKernelGGL(absmax_init_kernel, dim3(1), dim3(1), 0, st, bits);
+    hipLaunchKernelGGL(absmax_atomic_kernel, dim3(ew_grid((n - head) >> 2)), dim3(kEwThreads), 0, st, x, n, head, bits);
+    if (scale_out) hipLaunchKernelGGL(scale_from_amax_kernel, dim3(1), dim3(1), 0, st, amax_out, scale_out);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+int launch_absmax_partial(const float* x, int64_t n, float* partials, int* n_partials, hipStream_t st)
+{
+    const int head = head_of(x, n);
+    const int g = ew_grid((n - head) >> 2);
+    *n_partials = g;
+    hipLaunchKernelGGL(absmax_partial_kernel, dim3(g), dim3(kEwThreads), 0, st, x, n, head,
+                       reinterpret_cast<unsigned*>(partials));
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+int launch_quantize_amax(const float* x, int64_t n, const float* amax, int n_amax, float* amax_out, float* scale_out,
+                         int8_t* q, hipStream_t st)
+{
+    bool vec = ((reinterpret_cast<uintptr_t>(x) & 15) == 0) && ((reinterpret_cast<uintptr_t>(q) & 3) == 0);
+    if (vec)
+        hipLaunchKernelGGL(quantize_amax_kernel<true>, dim3(ew_grid(n >> 2)), dim3(kEwThreads), 0, st, x, n, amax,
+                           n_amax, amax_out, scale_out, q);
+    else
+        hipLaunchKernelGGL(quantize_amax_kernel<false>, dim3(ew_grid(n)), dim3(kEwThreads), 0, st, x, n, amax, n_amax,
+                           amax_out, scale_out, q);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 

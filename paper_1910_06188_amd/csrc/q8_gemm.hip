@@ -319,9 +319,16 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const int8_t* 
         }
     });
     if constexpr (!kPlain) {
-        if (ep.flags & 2u) {
+        if (ep.flags & 2u) {  // one atomic max per workgroup
+            __shared__ unsigned wave_amax[NW];
             amax = wave_max_u32(amax);
-            if (lane == 0) atomicMax(reinterpret_cast<unsigned*>(ep.out_amax), amax);
+            if (lane == 0) wave_amax[wave] = amax;
+            __syncthreads();
+            if (threadIdx.x == 0) {
+#pragma unroll
+                for (int w = 1; w < NW; ++w) amax = max(amax, wave_amax[w]);
+                atomicMax(reinterpret_cast<unsigned*>(ep.out_amax), amax);
+            }
         }
     }
 #endif

@@ -25,17 +25,19 @@ _lib = C.CDLL(LIB_PATH)
 OK = 0
 EPI_GELU, EPI_ABSMAX, EPI_REQUANT = 1, 2, 4
 MAX_K = 131071
+SCAL_WORK = 1026
 
 _vp, _i64, _i32, _u32 = C.c_void_p, C.c_int64, C.c_int, C.c_uint32
 
 _lib.q8_absmax.argtypes = [_vp, _i64, _vp, _vp, _vp]
 _lib.q8_scale_from_amax.argtypes = [_vp, _vp, _vp]
 _lib.q8_quantize.argtypes = [_vp, _i64, _vp, _vp, _vp]
+_lib.q8_quantize_amax.argtypes = [_vp, _i64, _vp, _i32, _vp, _vp, _vp, _vp]
 _lib.q8_linear.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _u32, _vp]
 _lib.q8_linear_f32.argtypes = [_vp, _vp, _vp, _vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _u32, _vp]
 _lib.q8_embedding.argtypes = [_vp, _vp, _i64, _i64, _vp, _i64, _vp, _i32, _vp, _vp]
 _lib.q8_embedding_sum3.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _vp]
-for _f in ("q8_absmax", "q8_scale_from_amax", "q8_quantize", "q8_linear", "q8_linear_f32", "q8_embedding",
+for _f in ("q8_absmax", "q8_scale_from_amax", "q8_quantize", "q8_quantize_amax", "q8_linear", "q8_linear_f32", "q8_embedding",
            "q8_embedding_sum3"):
     getattr(_lib, _f).restype = C.c_int
 _lib.q8_version.restype = C.c_char_p
@@ -99,6 +101,14 @@ def q8_quantize(x, scale, q, stream=None) -> None:
     _ck(_lib.q8_quantize(_ptr(x), x.numel(), _ptr(scale), _ptr(q), _stream(stream)), "q8_quantize")
 
 
+def q8_quantize_amax(x, amax, scale_out, q, amax_out=None, stream=None) -> None:
+    """S = 127 / max(amax[:]) (Eq. 3), then q = Quantize(x | S, 127) (Eq. 1), one launch."""
+    if q.numel() != x.numel():
+        raise ValueError("q8_quantize_amax: q and x differ in size")
+    _ck(_lib.q8_quantize_amax(_ptr(x), x.numel(), _ptr(amax), amax.numel(), _ptr(amax_out), _ptr(scale_out), _ptr(q),
+                              _stream(stream)), "q8_quantize_amax")
+
+
 def q8_linear(xq, wq, bias, sx, sw, y, n_groups=1, acc_out=None, out_amax=None, next_scale=None, flags=0,
               stream=None) -> None:
     """y = dequant(xq wq^T + quantized bias) (Section 3), optional fused epilogue stages."""
@@ -117,7 +127,7 @@ def q8_linear_f32(x, wq, bias, sw, xq_work, scal_work, y, n_groups=1, acc_out=No
     """Dynamic-quantization FC layer in one call: abs-max, quantize, GEMM, dequantize."""
     M, K = x.shape
     N, K2 = wq.shape
-    if K != K2 or y.numel() != M * N or xq_work.numel() < M * K or scal_work.numel() < 2:
+    if K != K2 or y.numel() != M * N or xq_work.numel() < M * K or scal_work.numel() < SCAL_WORK:
         raise ValueError("q8_linear_f32: shape mismatch")
     if sw.numel() != n_groups or (bias is not None and bias.numel() != N):
         raise ValueError("q8_linear_f32: scale/bias size mismatch")

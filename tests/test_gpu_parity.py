@@ -400,7 +400,7 @@ def test_linear_f32_one_call_equals_chain(q8):
     M, K = d["x"].shape
     N = d["W"].shape[0]
     xq_work = torch.empty(M * K, dtype=torch.int8, device="cuda")
-    scal = torch.zeros(2, device="cuda")
+    scal = torch.zeros(q8.SCAL_WORK, device="cuda")
     y = torch.empty((M, N), device="cuda")
     acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
     q8.q8_linear_f32(dev(d["x"]), dev(r["wq"]), dev(d["b"]), dev(r["sw"]), xq_work, scal, y, acc_out=acc)
@@ -408,6 +408,50 @@ def test_linear_f32_one_call_equals_chain(q8):
     np.testing.assert_array_equal(host(y), r["y"])
     np.testing.assert_array_equal(host(xq_work).reshape(M, K), r["xq"])
     assert host(scal)[1] == r["sx"]
+
+
+@pytest.mark.parametrize("n", [1, 7, 1000, 4_194_304, 12_582_912 + 3])
+def test_linear_f32_scales_and_codes_at_size(q8, n):
+    """The fused path's slot-based abs-max: scale and codes bit-exact for sizes from one
+    element to a full activation tensor (more slots than one trip fills)."""
+    g = synth.rng(500 + n % 71)
+    x = g.standard_normal(n, dtype=np.float32)
+    x[g.integers(0, n)] = np.float32(-9.5)
+    wq = torch.zeros((1, n), dtype=torch.int8, device="cuda") if n <= 131071 else None
+    xq_work = torch.empty(n, dtype=torch.int8, device="cuda")
+    scal = torch.full((q8.SCAL_WORK,), -3.0, device="cuda")
+    if wq is not None:     # through the one-call entry point (M = 1, K = n)
+        q8.q8_linear_f32(dev(x).view(1, n), wq, None, scalar(1.0), xq_work, scal, torch.empty((1, 1), device="cuda"))
+    else:                  # K too long for one GEMM row: M = n / 1024 rows of 1024
+        rows = n // 1024
+        x = x[: rows * 1024]
+        wq = torch.zeros((1, 1024), dtype=torch.int8, device="cuda")
+        xq_work = torch.empty(rows * 1024, dtype=torch.int8, device="cuda")
+        q8.q8_linear_f32(dev(x).view(rows, 1024), wq, None, scalar(1.0), xq_work, scal,
+                         torch.empty((rows, 1), device="cuda"))
+    s = O.scale(O.absmax(x))
+    sh = host(scal)
+    assert sh[0] == O.absmax(x) and sh[1] == s
+    np.testing.assert_array_equal(host(xq_work), O.quantize(x, s))
+
+
+def test_quantize_amax_one_value_and_partials(q8):
+    g = synth.rng(49)
+    x = g.standard_normal(100_003, dtype=np.float32)
+    a = O.absmax(x)
+    s = O.scale(a)
+    for amax_vals in ([float(a)], [0.1, float(a), 0.5, 0.0], list(np.abs(x[:700]).astype(float)) + [float(a)]):
+        scale_out, amax_out = scalar(-1.0), scalar(-1.0)
+        q = torch.empty(x.size, dtype=torch.int8, device="cuda")
+        q8.q8_quantize_amax(dev(x), dev(np.array(amax_vals, np.float32)), scale_out, q, amax_out=amax_out)
+        assert host(scale_out)[0] == s and host(amax_out)[0] == a
+        np.testing.assert_array_equal(host(q), O.quantize(x, s))
+    # all-zero abs-max: S = 1; misaligned views take the scalar kernel
+    scale_out = scalar(-1.0)
+    q = torch.empty(16, dtype=torch.int8, device="cuda")
+    q8.q8_quantize_amax(dev(x)[1:14], scalar(0.0), scale_out, q[1:14])
+    assert host(scale_out)[0] == 1.0
+    np.testing.assert_array_equal(host(q)[1:14], O.quantize(x[1:14], 1.0))
 
 
 def test_linear_is_deterministic(q8):
