@@ -100,16 +100,35 @@ __device__ __forceinline__ v4i make_rsrc(const void* base, unsigned bytes)
     return r;
 }
 
-// 16 bytes per lane from a buffer straight into LDS: lane l lands at lds_addr + 16*l.
-// rsrc, soff and lds_addr are wave-uniform.  Written as asm so that the compiler does not
-// pair every later LDS read with a full vmcnt(0) wait; the kernel orders these loads
-// against its LDS reads itself (s_waitcnt vmcnt + barrier).
-__device__ __forceinline__ void lds_dma16(v4i rsrc, unsigned voff, unsigned soff, unsigned lds_addr)
+// 16 bytes per lane from a buffer straight into LDS: lane l lands at M0 + OFF + 16*l and
+// reads global byte voff + soff + OFF (the instruction's immediate offset applies to both
+// sides).  rsrc, soff and the LDS address are wave-uniform.  Written as asm so that the
+// compiler does not pair every later LDS read with a full vmcnt(0) wait; the kernel orders
+// these loads against its LDS reads itself (s_waitcnt vmcnt + barrier).
+// lds_dma16_first also points M0 at the LDS block (one wait state before the load);
+// lds_dma16_next reuses M0, so a run of four 1 KiB blocks costs one M0 write: with a single
+// wave per SIMD every instruction issued between two MFMAs counts.
+__device__ __forceinline__ void lds_dma16_first(v4i rsrc, unsigned voff, unsigned soff, unsigned lds_addr)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                  :
                  : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
                  : "memory");
+}
+template <int OFF>
+__device__ __forceinline__ void lds_dma16_next(v4i rsrc, unsigned voff, unsigned soff)
+{
+    static_assert(OFF > 0 && OFF < 4096, "12-bit immediate");
+    asm volatile("buffer_load_dwordx4 %0, %1, %2 offen offset:%3 lds" : : "v"(voff), "s"(rsrc), "s"(soff), "n"(OFF) : "memory");
+}
+// i-th 1 KiB block of a run that starts at lds_run: blocks 4g..4g+3 share one M0 value.
+template <int I>
+__device__ __forceinline__ void lds_dma16_run(v4i rsrc, unsigned voff, unsigned soff, unsigned lds_run)
+{
+    if constexpr (I % 4 == 0)
+        lds_dma16_first(rsrc, voff, soff, lds_run + I * 1024);
+    else
+        lds_dma16_next<(I % 4) * 1024>(rsrc, voff - (I % 4) * 1024, soff);
 }
 
 // Compile-time loop: the body sees its index as a constant, so accumulator registers
@@ -204,11 +223,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const int8_t* 
         const v4i ra = make_rsrc(X, live ? bytes_a : 0u);
         const v4i rb = make_rsrc(W, live ? bytes_b : 0u);
         const unsigned koff = live ? (unsigned)(kt * kBK) : 0u;
-#pragma unroll
-        for (int i = 0; i < A_LOADS; ++i) lds_dma16(ra, a_off[i], koff, base + (wave * A_LOADS + i) * 1024);
-#pragma unroll
-        for (int i = 0; i < B_LOADS; ++i)
-            lds_dma16(rb, b_off[i], koff, base + A_BYTES + (wave * B_LOADS + i) * 1024);
+        static_for<0, A_LOADS>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            lds_dma16_run<i>(ra, a_off[i], koff, base + wave * A_LOADS * 1024);
+        });
+        static_for<0, B_LOADS>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            lds_dma16_run<i>(rb, b_off[i], koff, base + A_BYTES + wave * B_LOADS * 1024);
+        });
     };
 
     // Fragment addressing: lane l of a 32x32x32 MFMA supplies row (l % 32) and the
@@ -275,12 +297,41 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const int8_t* 
         __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
         // last k-step: every wave has left stage kt's ring slot -- refill it with stage
-        // kt+STAGES -- and fetch the first fragments of stage kt+1
-        issue_loads(kt + STAGES);
-        read_frags(kt + 1, 0, fa[0], fb[0]);
-        mfma_step(fa[(kKS - 1) & 1], fb[(kKS - 1) & 1]);
-        interleave<FM * FN, FM + FN, 0>();
-        __builtin_amdgcn_sched_barrier(0);
+        // kt+STAGES -- and fetch the first fragments of stage kt+1.  The global loads and LDS
+        // reads are placed by hand, a few behind each MFMA, so that issuing them never
+        // leaves the matrix pipe without a queued instruction.
+        {
+            const int kn = kt + STAGES;
+            const unsigned dst = lds_base + (unsigned)((kn % STAGES) * STAGE);
+            const bool live = kn < KT;  // past the end of K: empty descriptor, nothing is fetched
+            const v4i ra = make_rsrc(X, live ? bytes_a : 0u);
+            const v4i rb = make_rsrc(W, live ? bytes_b : 0u);
+            const unsigned koff = live ? (unsigned)(kn * kBK) : 0u;
+            const char* nbase = lds + ((kt + 1) % STAGES) * STAGE;
+            constexpr int L = (kKS - 1) & 1;
+            constexpr int NM = FM * FN, NR = FM + FN;
+            static_for<0, NM>([&](auto ic) {
+                constexpr int idx = decltype(ic)::value;
+                constexpr int i = idx / FN, j = idx % FN;
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[L][i], fb[L][j], acc[i][j], 0, 0, 0);
+                static_for<(LOADS * idx) / NM, (LOADS * (idx + 1)) / NM>([&](auto lc) {
+                    constexpr int l = decltype(lc)::value;
+                    if constexpr (l < A_LOADS)
+                        lds_dma16_run<l>(ra, a_off[l], koff, dst + wave * A_LOADS * 1024);
+                    else
+                        lds_dma16_run<l - A_LOADS>(rb, b_off[l - A_LOADS], koff,
+                                                   dst + A_BYTES + wave * B_LOADS * 1024);
+                });
+                static_for<(NR * idx) / NM, (NR * (idx + 1)) / NM>([&](auto rc) {
+                    constexpr int r = decltype(rc)::value;
+                    if constexpr (r < FM)
+                        fa[0][r] = *reinterpret_cast<const v4i*>(nbase + a_frag_off[r][0]);
+                    else
+                        fb[0][r - FM] = *reinterpret_cast<const v4i*>(nbase + b_frag_off[r - FM][0]);
+                });
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        }
     }
 
     // Epilogue.  Accumulator register e of lane l is row 8*(e/4) + 4*(l/32) + e%4 and
@@ -414,6 +465,8 @@ int launch_gemm_mfma(const int8_t* xq, const int8_t* wq, int64_t M64, int64_t N6
         case 2: return launch_tile<256, 256, 2, 4, 2>(xq, wq, M, N, K, group_m, ep, st);
         case 3: return launch_tile<128, 128, 2, 2, 4>(xq, wq, M, N, K, group_m, ep, st);
         case 4: return launch_tile<192, 256, 2, 2, 2>(xq, wq, M, N, K, group_m, ep, st);
+        case 5: return launch_tile<192, 192, 2, 2, 2>(xq, wq, M, N, K, group_m, ep, st);
+        case 6: return launch_tile<192, 192, 2, 2, 3>(xq, wq, M, N, K, group_m, ep, st);
         default: return 1;
     }
 }
