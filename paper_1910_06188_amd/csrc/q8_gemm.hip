@@ -144,41 +144,52 @@ __device__ __forceinline__ void static_for(F&& f)
 
 // Software-pipelined MFMA kernel.
 //
-// K is walked in stages of kBK = 128 bytes.  The LDS holds STAGES stage buffers in a ring.
-// A stage is four 32-byte k-steps; the fragments of the next k-step are read from LDS
-// while the MFMAs of the current one run, so that the matrix pipe never waits for an LDS
-// round trip, and the barrier sits before the last k-step, whose fragments are already in
-// registers, so the stage buffer can be refilled a whole stage ahead of its use:
+// K is walked in stages of kBK = 128 bytes, four 32-byte k-steps each.  The x tile (A) and
+// the w tile (B) each have their own ring of stage buffers in LDS: SA slots for A, SB for B.
 //
-//   k-steps 0..2 of stage t : ds_read fragments of the next k-step     || MFMAs
+//   k-steps 0..2 of stage t : ds_read fragments of the next k-step, and -- with SB = 3 -- the
+//                             B loads of stage t+3 into the B slot stage t-... left free at the
+//                             previous barrier                               || MFMAs
 //   wait: own reads of stage t done, own loads of stage t+1 landed;  barrier
-//   k-step 3 of stage t     : buffer_load stage t+STAGES -> ring slot of stage t,
-//                             ds_read fragments (t+1, k-step 0)         || MFMAs
+//   k-step 3 of stage t     : A loads of stage t+SA into the A slot of stage t (and, with
+//                             SB = 2, the B loads of stage t+2 likewise),
+//                             ds_read fragments (t+1, k-step 0)              || MFMAs
 //
-// Loads past the end of K go through an empty buffer descriptor (num_records = 0): the
-// hardware drops them and returns zeros, so the vmcnt bookkeeping is the same in every
-// trip and no memory is touched.
+// Why two ring depths: a wave that issues a global->LDS load is held until the texture
+// path accepts it (one 1 KiB wave load per ~64 cycles per wave when all four waves load),
+// and with one wave per SIMD nothing else feeds the matrix pipe meanwhile.  Measured: more
+// than one load per two MFMAs stalls the pipe.  A third B slot lets the B loads spread over
+// the first three k-steps, leaving only the A loads for the last one; where LDS cannot hold
+// it (SB = 2) all loads fall in the last k-step.
+//
+// Every memory operation of a k-step is placed by hand behind a given MFMA (LDS reads early,
+// global loads at least two MFMAs apart).  Loads past the end of K go through an empty
+// buffer descriptor (num_records = 0): the hardware drops them and returns zeros, so the
+// vmcnt bookkeeping is the same in every trip and no memory is touched.
 //
 // kPlain: fp32 output with no optional epilogue stage and no accumulator dump -- the
 // common case gets a kernel of its own so the optional stages cost it nothing.
-template <int BM, int BN, int WGM, int WGN, int STAGES, bool kPlain>
+template <int BM, int BN, int WGM, int WGN, int SB, bool kPlain>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const int8_t* __restrict__ X,
                                                                    const int8_t* __restrict__ W, int M, int N, int K,
                                                                    int tiles_n, int group_m, Epilogue ep)
 {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
+    constexpr int SA = 2;
     constexpr int NW = WGM * WGN;
     constexpr int TM = BM / WGM, TN = BN / WGN;  // wave tile
     constexpr int FM = TM / 32, FN = TN / 32;    // 32x32 MFMA blocks per wave tile
-    constexpr int A_BYTES = BM * kBK, B_BYTES = BN * kBK, STAGE = A_BYTES + B_BYTES;
+    constexpr int A_BYTES = BM * kBK, B_BYTES = BN * kBK;
+    constexpr int B_RING = SA * A_BYTES;                         // LDS offset of the B ring
+    constexpr int LDS_BYTES = SA * A_BYTES + SB * B_BYTES;
     constexpr int A_LOADS = BM / 8 / NW, B_LOADS = BN / 8 / NW;  // 1 KiB wave loads per stage
-    constexpr int LOADS = A_LOADS + B_LOADS;
     static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must split over the waves");
     static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be made of 32x32 blocks");
-    static_assert(STAGES >= 2 && (STAGES - 1) * LOADS <= 63, "vmcnt is a 6-bit counter");
-    static_assert(STAGES * STAGE <= 160 * 1024, "LDS is 160 KiB per compute unit");
+    static_assert(SB == 2 || SB == 3, "B ring depth");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS is 160 KiB per compute unit");
+    static_assert(A_LOADS + B_LOADS <= 63, "vmcnt is a 6-bit counter");
 
-    __shared__ __attribute__((aligned(1024))) char lds[STAGES * STAGE];
+    __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -217,27 +228,33 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const int8_t* 
     }
 
     const int KT = K / kBK;
-    auto issue_loads = [&](int kt) {
-        const unsigned base = lds_base + (unsigned)((kt % STAGES) * STAGE);
+    // Descriptor, k offset and LDS run of this wave's share of one operand tile of stage kt.
+    struct Src {
+        v4i rsrc;
+        unsigned koff, dst;
+    };
+    auto src_a = [&](int kt, int slot) {
         const bool live = kt < KT;  // past the end of K: empty descriptor, nothing is fetched
-        const v4i ra = make_rsrc(X, live ? bytes_a : 0u);
-        const v4i rb = make_rsrc(W, live ? bytes_b : 0u);
-        const unsigned koff = live ? (unsigned)(kt * kBK) : 0u;
-        static_for<0, A_LOADS>([&](auto ic) {
-            constexpr int i = decltype(ic)::value;
-            lds_dma16_run<i>(ra, a_off[i], koff, base + wave * A_LOADS * 1024);
-        });
-        static_for<0, B_LOADS>([&](auto ic) {
-            constexpr int i = decltype(ic)::value;
-            lds_dma16_run<i>(rb, b_off[i], koff, base + A_BYTES + wave * B_LOADS * 1024);
-        });
+        return Src{make_rsrc(X, live ? bytes_a : 0u), live ? (unsigned)(kt * kBK) : 0u,
+                   lds_base + (unsigned)(slot * A_BYTES + wave * A_LOADS * 1024)};
+    };
+    auto src_b = [&](int kt, int slot) {
+        const bool live = kt < KT;
+        return Src{make_rsrc(W, live ? bytes_b : 0u), live ? (unsigned)(kt * kBK) : 0u,
+                   lds_base + (unsigned)(B_RING + slot * B_BYTES + wave * B_LOADS * 1024)};
+    };
+    auto load_all_a = [&](const Src& q) {
+        static_for<0, A_LOADS>([&](auto ic) { lds_dma16_run<decltype(ic)::value>(q.rsrc, a_off[decltype(ic)::value], q.koff, q.dst); });
+    };
+    auto load_all_b = [&](const Src& q) {
+        static_for<0, B_LOADS>([&](auto ic) { lds_dma16_run<decltype(ic)::value>(q.rsrc, b_off[decltype(ic)::value], q.koff, q.dst); });
     };
 
     // Fragment addressing: lane l of a 32x32x32 MFMA supplies row (l % 32) and the
     // 16 k-bytes numbered (l / 32) of a 32-byte k-step, for both operands.
     const int wm = wave / WGN, wn = wave % WGN;
     const int l32 = lane & 31, hi = lane >> 5;
-    int a_frag_off[FM][kKS], b_frag_off[FN][kKS];  // [block][k-step] byte offset inside a stage
+    int a_frag_off[FM][kKS], b_frag_off[FN][kKS];  // [block][k-step] byte offset inside a stage slot
 #pragma unroll
     for (int f = 0; f < FM; ++f) {
         int r = wm * TM + f * 32 + l32;
@@ -249,7 +266,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const int8_t* 
         int r = wn * TN + f * 32 + l32;
 #pragma unroll
         for (int ks = 0; ks < kKS; ++ks)
-            b_frag_off[f][ks] = A_BYTES + r * kBK + (((ks * 2 + hi) ^ swizzle_of_row(r)) << 4);
+            b_frag_off[f][ks] = B_RING + r * kBK + (((ks * 2 + hi) ^ swizzle_of_row(r)) << 4);
     }
 
     v16i acc[FM][FN];
@@ -261,77 +278,93 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const int8_t* 
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
 
     v4i fa[2][FM], fb[2][FN];  // fragments of the current / next k-step, double buffered in registers
-    auto read_frags = [&](int kt, int ks, v4i* a, v4i* b) {
-        const char* base = lds + (kt % STAGES) * STAGE;
-#pragma unroll
-        for (int f = 0; f < FM; ++f) a[f] = *reinterpret_cast<const v4i*>(base + a_frag_off[f][ks]);
-#pragma unroll
-        for (int f = 0; f < FN; ++f) b[f] = *reinterpret_cast<const v4i*>(base + b_frag_off[f][ks]);
-    };
-    auto mfma_step = [&](const v4i* a, const v4i* b) {
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
-    };
 
-#pragma unroll
-    for (int s = 0; s < STAGES; ++s) issue_loads(s);
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm((STAGES - 1) * LOADS));  // stage 0 landed
+    // Prologue: stages 0 and 1 of both operands; wait for stage 0.
+    load_all_a(src_a(0, 0));
+    load_all_b(src_b(0, 0));
+    load_all_a(src_a(1, 1));
+    load_all_b(src_b(1, 1));
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(A_LOADS + B_LOADS));
     __syncthreads();
-    read_frags(0, 0, fa[0], fb[0]);
-
-    for (int kt = 0; kt < KT; ++kt) {
-        // all k-steps but the last: next fragments in flight while the matrix pipe works
 #pragma unroll
-        for (int ks = 0; ks < kKS - 1; ++ks) {
-            read_frags(kt, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
-            mfma_step(fa[ks & 1], fb[ks & 1]);
-            interleave<FM * FN, FM + FN, 0>();
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        // own LDS reads of stage kt are complete and own loads of stage kt+1 have landed
-        // (the STAGES-2 younger stages may still be in flight)
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((STAGES - 2) * LOADS));
-        __syncthreads();
-        __builtin_amdgcn_sched_barrier(0);
-        // last k-step: every wave has left stage kt's ring slot -- refill it with stage
-        // kt+STAGES -- and fetch the first fragments of stage kt+1.  The global loads and LDS
-        // reads are placed by hand, a few behind each MFMA, so that issuing them never
-        // leaves the matrix pipe without a queued instruction.
-        {
-            const int kn = kt + STAGES;
-            const unsigned dst = lds_base + (unsigned)((kn % STAGES) * STAGE);
-            const bool live = kn < KT;  // past the end of K: empty descriptor, nothing is fetched
-            const v4i ra = make_rsrc(X, live ? bytes_a : 0u);
-            const v4i rb = make_rsrc(W, live ? bytes_b : 0u);
-            const unsigned koff = live ? (unsigned)(kn * kBK) : 0u;
-            const char* nbase = lds + ((kt + 1) % STAGES) * STAGE;
-            constexpr int L = (kKS - 1) & 1;
-            constexpr int NM = FM * FN, NR = FM + FN;
+    for (int f = 0; f < FM; ++f) fa[0][f] = *reinterpret_cast<const v4i*>(lds + a_frag_off[f][0]);
+#pragma unroll
+    for (int f = 0; f < FN; ++f) fb[0][f] = *reinterpret_cast<const v4i*>(lds + b_frag_off[f][0]);
+
+    constexpr int NM = FM * FN, NR = FM + FN;
+    int a_slot = 0, b_slot = 0;  // ring slots of the stage being consumed
+    for (int kt = 0; kt < KT; ++kt) {
+        const int a_next = a_slot ^ 1;
+        const int b_next = (b_slot + 1 == SB) ? 0 : b_slot + 1;
+        const int b_prev = (b_slot == 0) ? SB - 1 : b_slot - 1;
+        const char* cur_a = lds + a_slot * A_BYTES;
+        const char* cur_b = lds + b_slot * B_BYTES;
+        // SB = 3: the B slot of stage kt-1 was left by every wave at the last barrier (at
+        // kt = 0 it has not been used yet); it takes the B tile of stage kt+2
+        const Src qb3 = src_b(kt + 2, b_prev);
+        // k-steps 0..2
+        static_for<0, kKS - 1>([&](auto ksc) {
+            constexpr int ks = decltype(ksc)::value;
+            constexpr int C = ks & 1, Nx = (ks + 1) & 1;
+            constexpr int bl0 = (SB == 3) ? (B_LOADS * ks) / (kKS - 1) : 0;
+            constexpr int bl1 = (SB == 3) ? (B_LOADS * (ks + 1)) / (kKS - 1) : 0;
+            constexpr int ND = bl1 - bl0;
             static_for<0, NM>([&](auto ic) {
                 constexpr int idx = decltype(ic)::value;
                 constexpr int i = idx / FN, j = idx % FN;
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[L][i], fb[L][j], acc[i][j], 0, 0, 0);
-                static_for<(LOADS * idx) / NM, (LOADS * (idx + 1)) / NM>([&](auto lc) {
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[C][i], fb[C][j], acc[i][j], 0, 0, 0);
+                // fragments of k-step ks+1: two reads behind each of the first MFMAs
+                static_for<2 * idx, (2 * idx + 2 < NR ? 2 * idx + 2 : NR)>([&](auto rc) {
+                    constexpr int r = decltype(rc)::value;
+                    if constexpr (r < FM)
+                        fa[Nx][r] = *reinterpret_cast<const v4i*>(cur_a + a_frag_off[r][ks + 1]);
+                    else
+                        fb[Nx][r - FM] = *reinterpret_cast<const v4i*>(cur_b + b_frag_off[r - FM][ks + 1]);
+                });
+                // B loads, spread over the k-step
+                static_for<(ND * idx) / NM, (ND * (idx + 1)) / NM>([&](auto lc) {
+                    constexpr int l = bl0 + decltype(lc)::value;
+                    lds_dma16_run<l>(qb3.rsrc, b_off[l], qb3.koff, qb3.dst);
+                });
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        });
+        // own LDS reads of stage kt are complete and own loads of stage kt+1 have landed;
+        // with SB = 3 the B loads just issued may still be in flight
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(SB == 3 ? B_LOADS : 0));
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        // last k-step: every wave has left stage kt's slots
+        {
+            const Src qa = src_a(kt + SA, a_slot);
+            const Src qb2 = src_b(kt + 2, b_slot);  // SB = 2 only
+            const char* nxt_a = lds + a_next * A_BYTES;
+            const char* nxt_b = lds + b_next * B_BYTES;
+            constexpr int C = (kKS - 1) & 1;
+            constexpr int ND = A_LOADS + (SB == 2 ? B_LOADS : 0);
+            static_for<0, NM>([&](auto ic) {
+                constexpr int idx = decltype(ic)::value;
+                constexpr int i = idx / FN, j = idx % FN;
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[C][i], fb[C][j], acc[i][j], 0, 0, 0);
+                static_for<(ND * idx) / NM, (ND * (idx + 1)) / NM>([&](auto lc) {
                     constexpr int l = decltype(lc)::value;
                     if constexpr (l < A_LOADS)
-                        lds_dma16_run<l>(ra, a_off[l], koff, dst + wave * A_LOADS * 1024);
+                        lds_dma16_run<l>(qa.rsrc, a_off[l], qa.koff, qa.dst);
                     else
-                        lds_dma16_run<l - A_LOADS>(rb, b_off[l - A_LOADS], koff,
-                                                   dst + A_BYTES + wave * B_LOADS * 1024);
+                        lds_dma16_run<l - A_LOADS>(qb2.rsrc, b_off[l - A_LOADS], qb2.koff, qb2.dst);
                 });
                 static_for<(NR * idx) / NM, (NR * (idx + 1)) / NM>([&](auto rc) {
                     constexpr int r = decltype(rc)::value;
                     if constexpr (r < FM)
-                        fa[0][r] = *reinterpret_cast<const v4i*>(nbase + a_frag_off[r][0]);
+                        fa[0][r] = *reinterpret_cast<const v4i*>(nxt_a + a_frag_off[r][0]);
                     else
-                        fb[0][r - FM] = *reinterpret_cast<const v4i*>(nbase + b_frag_off[r - FM][0]);
+                        fb[0][r - FM] = *reinterpret_cast<const v4i*>(nxt_b + b_frag_off[r - FM][0]);
                 });
                 __builtin_amdgcn_sched_barrier(0);
             });
         }
+        a_slot = a_next;
+        b_slot = b_next;
     }
 
     // Epilogue.  Accumulator register e of lane l is row 8*(e/4) + 4*(l/32) + e%4 and
@@ -340,38 +373,82 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const int8_t* 
     float next_scale = 0.0f;
     if constexpr (!kPlain) next_scale = (ep.flags & 4u) ? ep.next_scale[0] : 0.0f;
     unsigned amax = 0u;
-    static_for<0, FN>([&](auto jc) {
-        constexpr int j = decltype(jc)::value;
-        const int n = n0 + wn * TN + j * 32 + l32;
-        if (n < N) {
+    // A tile that lies wholly inside y (every tile of the BERT shapes) takes stores with a
+    // per-lane column offset in a VGPR and the row offset in an SGPR: about six instructions
+    // per element.  With one wave per SIMD the epilogue is bound by instruction issue, and
+    // the bounds-checked path below costs twice as many.
+    const bool interior = (m0 + BM <= M) && (n0 + BN <= N) && ((int64_t)M * N * 4 < ((int64_t)1 << 31));
+    if (interior) {
+        const bool out_i8 = !kPlain && (ep.flags & 4u);
+        const int esize = out_i8 ? 1 : 4;
+        const __amdgpu_buffer_rsrc_t ry =
+            __builtin_amdgcn_make_buffer_rsrc(ep.y, 0, (int)((unsigned)M * (unsigned)N * (unsigned)esize), 0x00020000);
+        const __amdgpu_buffer_rsrc_t racc = __builtin_amdgcn_make_buffer_rsrc(
+            ep.acc_out, 0, ep.acc_out ? (int)((unsigned)M * (unsigned)N * 4u) : 0, 0x00020000);
+        const int row0 = m0 + wm * TM + 4 * hi;  // first row this lane stores
+        static_for<0, FN>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            const int n = n0 + wn * TN + j * 32 + l32;
             const ColConst cc = col_const(ep, n, sx);
+            const int elem0 = row0 * N + n;
             static_for<0, FM>([&](auto ic) {
                 constexpr int i = decltype(ic)::value;
-                const int mb = m0 + wm * TM + i * 32 + 4 * hi;
-                if constexpr (kPlain) {
-                    float* yp = reinterpret_cast<float*>(ep.y) + (int64_t)mb * N + n;
-                    static_for<0, 16>([&](auto ec) {
-                        constexpr int e = decltype(ec)::value;
-                        constexpr int dm = 8 * (e >> 2) + (e & 3);
-                        if (mb + dm < M) yp[(int64_t)dm * N] = (float)(acc[i][j][e] + cc.bq) * cc.r;
-                    });
-                } else {
-                    static_for<0, 16>([&](auto ec) {
-                        constexpr int e = decltype(ec)::value;
-                        const int m = mb + 8 * (e >> 2) + (e & 3);
-                        if (m < M) {
-                            unsigned ab =
-                                epilogue_store(ep, (int64_t)m * N + n, acc[i][j][e] + cc.bq, cc.r, next_scale);
-                            amax = max(amax, ab);
-                        }
-                    });
-                }
+                static_for<0, 16>([&](auto ec) {
+                    constexpr int e = decltype(ec)::value;
+                    constexpr int dm = i * 32 + 8 * (e >> 2) + (e & 3);
+                    const int row_elems = dm * N;  // wave-uniform: lives in an SGPR
+                    const int a = acc[i][j][e] + cc.bq;
+                    float yv = (float)a * cc.r;
+                    if constexpr (kPlain) {
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(yv), ry, elem0 * 4, row_elems * 4, 0);
+                    } else {
+                        if (ep.acc_out) __builtin_amdgcn_raw_buffer_store_b32((unsigned)a, racc, elem0 * 4, row_elems * 4, 0);
+                        if (ep.flags & 1u) yv = gelu_erf(yv);
+                        amax = max(amax, f32_abs_bits(yv));
+                        if (out_i8)
+                            __builtin_amdgcn_raw_buffer_store_b8((unsigned char)quantize_code(yv, next_scale), ry, elem0,
+                                                                 row_elems, 0);
+                        else
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(yv), ry, elem0 * 4, row_elems * 4, 0);
+                    }
+                });
             });
-        }
-    });
+        });
+    } else {
+        static_for<0, FN>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            const int n = n0 + wn * TN + j * 32 + l32;
+            if (n < N) {
+                const ColConst cc = col_const(ep, n, sx);
+                static_for<0, FM>([&](auto ic) {
+                    constexpr int i = decltype(ic)::value;
+                    const int mb = m0 + wm * TM + i * 32 + 4 * hi;
+                    if constexpr (kPlain) {
+                        float* yp = reinterpret_cast<float*>(ep.y) + (int64_t)mb * N + n;
+                        static_for<0, 16>([&](auto ec) {
+                            constexpr int e = decltype(ec)::value;
+                            constexpr int dm = 8 * (e >> 2) + (e & 3);
+                            if (mb + dm < M) yp[(int64_t)dm * N] = (float)(acc[i][j][e] + cc.bq) * cc.r;
+                        });
+                    } else {
+                        static_for<0, 16>([&](auto ec) {
+                            constexpr int e = decltype(ec)::value;
+                            const int m = mb + 8 * (e >> 2) + (e & 3);
+                            if (m < M) {
+                                unsigned ab =
+                                    epilogue_store(ep, (int64_t)m * N + n, acc[i][j][e] + cc.bq, cc.r, next_scale);
+                                amax = max(amax, ab);
+                            }
+                        });
+                    }
+                });
+            }
+        });
+    }
     if constexpr (!kPlain) {
-        if (ep.flags & 2u) {  // one atomic max per workgroup
-            __shared__ unsigned wave_amax[NW];
+        if (ep.flags & 2u) {  // one atomic max per workgroup; the stage buffers are dead by now
+            unsigned* wave_amax = reinterpret_cast<unsigned*>(lds);
+            __syncthreads();
             amax = wave_max_u32(amax);
             if (lane == 0) wave_amax[wave] = amax;
             __syncthreads();
@@ -423,17 +500,17 @@ bool gemm_mfma_eligible(const int8_t* xq, const int8_t* wq, int64_t M, int64_t N
     return M > 0 && N > 0;
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES>
+template <int BM, int BN, int WGM, int WGN, int SB>
 static int launch_tile(const int8_t* xq, const int8_t* wq, int M, int N, int K, int group_m, const Epilogue& ep,
                        hipStream_t st)
 {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const dim3 grid(tiles_m * tiles_n), block(WGM * WGN * 64);
     if (ep.flags == 0u && ep.acc_out == nullptr)
-        hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WGM, WGN, STAGES, true>), grid, block, 0, st, xq, wq, M, N, K, tiles_n,
+        hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WGM, WGN, SB, true>), grid, block, 0, st, xq, wq, M, N, K, tiles_n,
                            group_m, ep);
     else
-        hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WGM, WGN, STAGES, false>), grid, block, 0, st, xq, wq, M, N, K, tiles_n,
+        hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WGM, WGN, SB, false>), grid, block, 0, st, xq, wq, M, N, K, tiles_n,
                            group_m, ep);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
@@ -461,12 +538,12 @@ int launch_gemm_mfma(const int8_t* xq, const int8_t* wq, int64_t M64, int64_t N6
     }
     const int group_m = 8;
     switch (v) {
-        case 1: return launch_tile<256, 256, 2, 2, 2>(xq, wq, M, N, K, group_m, ep, st);
-        case 2: return launch_tile<256, 256, 2, 4, 2>(xq, wq, M, N, K, group_m, ep, st);
-        case 3: return launch_tile<128, 128, 2, 2, 4>(xq, wq, M, N, K, group_m, ep, st);
-        case 4: return launch_tile<192, 256, 2, 2, 2>(xq, wq, M, N, K, group_m, ep, st);
-        case 5: return launch_tile<192, 192, 2, 2, 2>(xq, wq, M, N, K, group_m, ep, st);
-        case 6: return launch_tile<192, 192, 2, 2, 3>(xq, wq, M, N, K, group_m, ep, st);
+        case 1: return launch_tile<256, 256, 2, 2, 3>(xq, wq, M, N, K, group_m, ep, st);
+        case 2: return launch_tile<256, 256, 2, 4, 3>(xq, wq, M, N, K, group_m, ep, st);
+        case 3: return launch_tile<128, 128, 2, 2, 3>(xq, wq, M, N, K, group_m, ep, st);
+        case 4: return launch_tile<192, 256, 2, 2, 3>(xq, wq, M, N, K, group_m, ep, st);
+        case 5: return launch_tile<192, 256, 2, 2, 2>(xq, wq, M, N, K, group_m, ep, st);
+        case 6: return launch_tile<256, 256, 2, 4, 2>(xq, wq, M, N, K, group_m, ep, st);
         default: return 1;
     }
 }
