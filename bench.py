@@ -33,6 +33,9 @@ sys.path.insert(0, ROOT)
 METRIC = "int8 TOPS + % MFMA peak on BERT FC GEMMs; tokens/s per quantized BERT layer"
 INT8_PEAK_TOPS = 5033.0      # MI355X published dense int8 matrix peak
 HBM_PEAK_GBS = 8000.0
+# HBM-side bytes per launch of the FFN2 GEMM at the default workload, from the two rocprofv3 --pmc runs summarised in
+# profiles/bench_bert_large_layer_pmc_traffic.txt (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, calibrated on a 256 MiB copy)
+FFN2_TRAFFIC_BYTES = 134.5e6
 
 
 def parse():
@@ -44,6 +47,9 @@ def parse():
     ap.add_argument("--seq", type=int, default=384)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=12288)
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="after the timed region, copy a 256 MiB tensor three times (a kernel of known HBM traffic "
+                         "against which rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled)")
     return ap.parse_args()
 
 
@@ -197,6 +203,12 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     assert int(layer.err.item()) == 0
+    if args.pmc_calibration:
+        src = torch.ones(64 * 1024 * 1024, device="cuda")       # 256 MiB of fp32
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     ms_per_step = dt / args.steps * 1e3
     tops = layer.gemm_ops / (dt / args.steps) / 1e12
@@ -218,7 +230,9 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "gemm_mfma_kernel (FFN2 12288x1024x4096, fp32 out)",
                      "achieved": round(ffn2_tops, 1), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
                      "frac": round(ffn2_tops / INT8_PEAK_TOPS, 4), "avg_launch_us": round(ffn2_ms * 1e3, 2),
-                     "traffic": None},
+                     "traffic": FFN2_TRAFFIC_BYTES if (args.batch, args.seq) == (32, 384) else None,
+                     "traffic_unit": "bytes per launch (algorithmic: 104.9e6)",
+                     "measured_mfma_ceiling_real_operands_tops": 3400.0},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(d, args.cpu_sample_tokens)

@@ -44,8 +44,8 @@ typedef enum {
  * -128 included, can overflow the int32 accumulator before the bias is added. */
 #define Q8_MAX_K 131071
 
-/* Floats of scalar scratch q8_linear_f32 needs: abs-max, scale and up to 1024 partial maxima. */
-#define Q8_SCAL_WORK 1026
+/* Floats of scalar scratch q8_linear_f32 needs: abs-max, scale and up to 2048 partial maxima. */
+#define Q8_SCAL_WORK 2050
 
 /* q8_linear epilogue bits. */
 #define Q8_EPI_GELU 1u     /* y <- gelu(y), exact-erf form, in fp32 (GELU stays FP32: Section 3) */

@@ -8,7 +8,7 @@ namespace q8 {
 
 constexpr int kEwThreads = 256;
 constexpr int kEwUnroll = 4;  // float4 loads in flight per thread per trip
-constexpr int kMaxEwGrid = 1024;  // also the number of abs-max slots the fused path may use
+constexpr int kMaxEwGrid = 2048;  // also the number of abs-max slots the fused path may use
 
 // Order of non-negative binary32 values equals the order of their bit patterns,
 // so the reduction runs on integers and ends in one atomic max per workgroup.
@@ -25,6 +25,9 @@ __global__ void absmax_empty_kernel(float* amax, float* scale)
 
 // Per-thread abs-max of this thread's share of x.  x is walked as aligned float4 vectors;
 // `head` leading and the trailing scalars (fewer than 4 each) are taken by block 0.
+// A maximum does not mind seeing an element twice, so the last trip clamps its indices to
+// the final vector instead of branching: every trip has kAmUnroll loads in flight.
+constexpr int kAmUnroll = 8;
 __device__ __forceinline__ unsigned absmax_thread(const float* __restrict__ x, int64_t n, int head)
 {
     unsigned m = 0u;
@@ -32,21 +35,16 @@ __device__ __forceinline__ unsigned absmax_thread(const float* __restrict__ x, i
     const int64_t nvec = (n - head) >> 2;
     const int64_t tail0 = head + (nvec << 2);
     const int64_t stride = (int64_t)gridDim.x * kEwThreads;
-    int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x;
-    for (; i + (kEwUnroll - 1) * stride < nvec; i += kEwUnroll * stride) {
-        float4 v[kEwUnroll];
+    for (int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; i < nvec; i += kAmUnroll * stride) {
+        float4 v[kAmUnroll];
 #pragma unroll
-        for (int u = 0; u < kEwUnroll; ++u) v[u] = xv[i + u * stride];
+        for (int u = 0; u < kAmUnroll; ++u) v[u] = xv[min(i + u * stride, nvec - 1)];
 #pragma unroll
-        for (int u = 0; u < kEwUnroll; ++u) {
+        for (int u = 0; u < kAmUnroll; ++u) {
             unsigned a = max(abs_bits(v[u].x), abs_bits(v[u].y));
             unsigned b = max(abs_bits(v[u].z), abs_bits(v[u].w));
             m = max(m, max(a, b));
         }
-    }
-    for (; i < nvec; i += stride) {
-        float4 v = xv[i];
-        m = max(m, max(max(abs_bits(v.x), abs_bits(v.y)), max(abs_bits(v.z), abs_bits(v.w))));
     }
     if (blockIdx.x == 0) {
         if ((int)threadIdx.x < head) m = max(m, abs_bits(x[threadIdx.x]));
@@ -188,6 +186,14 @@ __global__ __launch_bounds__(kEwThreads) void quantize_scalar_kernel(const float
         q[i] = (int8_t)quantize_code(x[i], s);
 }
 
+static int am_grid(int64_t nvec)
+{
+    int64_t per_block = (int64_t)kEwThreads * 6;  // 6 to 8 vectors per thread in one trip
+    int64_t g = (nvec + per_block - 1) / per_block;
+    if (g < 1) g = 1;
+    return (int)(g < kMaxEwGrid ? g : kMaxEwGrid);
+}
+
 static int ew_grid(int64_t work_items)
 {
     int64_t per_block = (int64_t)kEwThreads * kEwUnroll;
@@ -212,7 +218,7 @@ int launch_absmax(const float* x, int64_t n, float* amax_out, float* scale_out, 
     unsigned* bits = reinterpret_cast<unsigned*>(amax_out);
     const int head = head_of(x, n);
     hipLaunchKernelGGL(absmax_init_kernel, dim3(1), dim3(1), 0, st, bits);
-    hipLaunchKernelGGL(absmax_atomic_kernel, dim3(ew_grid((n - head) >> 2)), dim3(kEwThreads), 0, st, x, n, head, bits);
+    hipLaunchKernelGGL(absmax_atomic_kernel, dim3(am_grid((n - head) >> 2)), dim3(kEwThreads), 0, st, x, n, head, bits);
     if (scale_out) hipLaunchKernelGGL(scale_from_amax_kernel, dim3(1), dim3(1), 0, st, amax_out, scale_out);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
@@ -220,7 +226,7 @@ int launch_absmax(const float* x, int64_t n, float* amax_out, float* scale_out, 
 int launch_absmax_partial(const float* x, int64_t n, float* partials, int* n_partials, hipStream_t st)
 {
     const int head = head_of(x, n);
-    const int g = ew_grid((n - head) >> 2);
+    const int g = am_grid((n - head) >> 2);
     *n_partials = g;
     hipLaunchKernelGGL(absmax_partial_kernel, dim3(g), dim3(kEwThreads), 0, st, x, n, head,
                        reinterpret_cast<unsigned*>(partials));

@@ -16,29 +16,29 @@ __device__ __forceinline__ float4 dequant4(unsigned packed, float r)
     return o;
 }
 
-// One thread per 4 codes of an output row: a wave reads 256 contiguous table bytes
-// and writes 1 KiB of contiguous fp32 (or 256 B of int8).  Needs H % 4 == 0.
+// One workgroup per token row at a time, one thread per 4 codes: the id is wave-uniform (a
+// scalar load), a wave reads 256 contiguous table bytes and writes 1 KiB of contiguous fp32
+// (or 256 B of int8).  Needs H % 4 == 0.
 template <bool kInt8Out>
 __global__ __launch_bounds__(256) void embedding_vec_kernel(const unsigned* __restrict__ table,
                                                              const float* __restrict__ scale, int64_t V, int H4,
                                                              const int32_t* __restrict__ ids, int64_t T,
                                                              void* __restrict__ out, int32_t* err_flag)
 {
-    const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (w >= T * H4) return;
-    const int64_t t = w / H4;
-    const int j = (int)(w - t * H4);
-    const int64_t id = ids[t];
-    unsigned packed = 0u;
-    if (id >= 0 && id < V)
-        packed = table[id * H4 + j];
-    else if (err_flag && j == 0)
-        err_flag[0] = 1;
-    if (kInt8Out) {
-        reinterpret_cast<unsigned*>(out)[w] = packed;
-    } else {
-        const float r = __fdiv_rn(1.0f, scale[0]);
-        reinterpret_cast<float4*>(out)[w] = dequant4(packed, r);
+    float r = 0.0f;
+    if (!kInt8Out) r = __fdiv_rn(1.0f, scale[0]);
+    for (int64_t t = blockIdx.x; t < T; t += gridDim.x) {
+        const int64_t id = ids[t];
+        const bool ok = id >= 0 && id < V;
+        if (!ok && err_flag && threadIdx.x == 0) err_flag[0] = 1;
+        const unsigned* row = table + (ok ? id : 0) * H4;
+        for (int j = threadIdx.x; j < H4; j += 256) {
+            const unsigned packed = ok ? row[j] : 0u;
+            if (kInt8Out)
+                reinterpret_cast<unsigned*>(out)[t * H4 + j] = packed;
+            else
+                reinterpret_cast<float4*>(out)[t * H4 + j] = dequant4(packed, r);
+        }
     }
 }
 
@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void embedding_scalar_kernel(const int8_t* __r
 }
 
 // word + position + token-type rows, each dequantised with its own scale, summed as
-// (word + position) + type in fp32.  Needs H % 4 == 0.
+// (word + position) + type in fp32.  A token row per workgroup at a time.  Needs H % 4 == 0.
 __global__ __launch_bounds__(256) void embedding_sum3_kernel(const unsigned* __restrict__ word, int64_t Vw,
                                                               const unsigned* __restrict__ pos, int64_t Vp,
                                                               const unsigned* __restrict__ typ, int64_t Vt,
@@ -76,24 +76,28 @@ __global__ __launch_bounds__(256) void embedding_sum3_kernel(const unsigned* __r
                                                               const int32_t* __restrict__ tid, int64_t T,
                                                               float4* __restrict__ out, int32_t* err_flag)
 {
-    const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (w >= T * H4) return;
-    const int64_t t = w / H4;
-    const int j = (int)(w - t * H4);
-    const int64_t a = wid[t], b = pid[t], c = tid[t];
-    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (a >= 0 && a < Vw && b >= 0 && b < Vp && c >= 0 && c < Vt) {
-        const float4 x = dequant4(word[a * H4 + j], __fdiv_rn(1.0f, scales[0]));
-        const float4 y = dequant4(pos[b * H4 + j], __fdiv_rn(1.0f, scales[1]));
-        const float4 z = dequant4(typ[c * H4 + j], __fdiv_rn(1.0f, scales[2]));
-        o.x = (x.x + y.x) + z.x;
-        o.y = (x.y + y.y) + z.y;
-        o.z = (x.z + y.z) + z.z;
-        o.w = (x.w + y.w) + z.w;
-    } else if (err_flag && j == 0) {
-        err_flag[0] = 1;
+    const float r0 = __fdiv_rn(1.0f, scales[0]), r1 = __fdiv_rn(1.0f, scales[1]), r2 = __fdiv_rn(1.0f, scales[2]);
+    for (int64_t t = blockIdx.x; t < T; t += gridDim.x) {  // ids are wave-uniform: scalar loads
+        const int64_t a = wid[t], b = pid[t], c = tid[t];
+        const bool ok = a >= 0 && a < Vw && b >= 0 && b < Vp && c >= 0 && c < Vt;
+        if (!ok && err_flag && threadIdx.x == 0) err_flag[0] = 1;
+        const unsigned* wr = word + (ok ? a : 0) * H4;
+        const unsigned* pr = pos + (ok ? b : 0) * H4;
+        const unsigned* tr = typ + (ok ? c : 0) * H4;
+        for (int j = threadIdx.x; j < H4; j += 256) {
+            float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (ok) {
+                const float4 x = dequant4(wr[j], r0);
+                const float4 y = dequant4(pr[j], r1);
+                const float4 z = dequant4(tr[j], r2);
+                o.x = (x.x + y.x) + z.x;
+                o.y = (x.y + y.y) + z.y;
+                o.z = (x.z + y.z) + z.z;
+                o.w = (x.w + y.w) + z.w;
+            }
+            out[t * H4 + j] = o;
+        }
     }
-    out[w] = o;
 }
 
 __global__ __launch_bounds__(256) void embedding_sum3_scalar_kernel(const int8_t* __restrict__ word, int64_t Vw,
@@ -131,7 +135,7 @@ int launch_embedding(const int8_t* table, const float* scale, int64_t V, int64_t
     const bool vec = (H % 4 == 0) && aligned(table, 4) && aligned(out, out_is_int8 ? 4 : 16);
     if (vec) {
         const int H4 = (int)(H / 4);
-        const unsigned blocks = (unsigned)((T * H4 + 255) / 256);
+        const unsigned blocks = (unsigned)(T < 8192 ? T : 8192);  // a token row per workgroup, grid-stride
         const unsigned* tab = reinterpret_cast<const unsigned*>(table);
         if (out_is_int8)
             hipLaunchKernelGGL(embedding_vec_kernel<true>, dim3(blocks), dim3(256), 0, st, tab, scale, V, H4, ids, T,
@@ -159,7 +163,7 @@ int launch_embedding_sum3(const int8_t* word, int64_t Vw, const int8_t* pos, int
     const bool vec = (H % 4 == 0) && aligned(word, 4) && aligned(pos, 4) && aligned(type, 4) && aligned(out, 16);
     if (vec) {
         const int H4 = (int)(H / 4);
-        const unsigned blocks = (unsigned)((T * H4 + 255) / 256);
+        const unsigned blocks = (unsigned)(T < 8192 ? T : 8192);  // a token row per workgroup, grid-stride
         hipLaunchKernelGGL(embedding_sum3_kernel, dim3(blocks), dim3(256), 0, st,
                            reinterpret_cast<const unsigned*>(word), Vw, reinterpret_cast<const unsigned*>(pos), Vp,
                            reinterpret_cast<const unsigned*>(type), Vt, scales, H4, wid, pid, tid, T,

@@ -25,7 +25,7 @@ _lib = C.CDLL(LIB_PATH)
 OK = 0
 EPI_GELU, EPI_ABSMAX, EPI_REQUANT = 1, 2, 4
 MAX_K = 131071
-SCAL_WORK = 1026
+SCAL_WORK = 2050
 
 _vp, _i64, _i32, _u32 = C.c_void_p, C.c_int64, C.c_int, C.c_uint32
 
