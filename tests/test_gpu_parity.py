@@ -432,6 +432,49 @@ def test_linear_static_activation_scale(q8):
     assert_rel(r["y"], ref["y"])
 
 
+def test_static_scale_ffn_chain_int8_to_int8(q8):
+    """The paper's own inference mode keeps a stored activation scale (Eq. 4), so FFN1 can
+    emit int8 directly (GELU + requantize in the epilogue) and FFN2 consumes it with no
+    quantize pass.  Checked stage by stage: each stage's oracle is fed the GPU's own output
+    of the stage before it."""
+    g = synth.rng(52)
+    M, H, F = 512, 256, 1024
+    d = synth.ffn_block(53, M, H, F)
+    x, W1, b1, W2, b2 = d["x"], d["W1"] * np.float32(4.0), d["b1"], d["W2"], d["b2"]
+    w1q, s1 = O.quantize_tensor(W1)
+    w2q, s2 = O.quantize_tensor(W2)
+    sx = np.float32(127.0 / 4.5)            # stored scales, as a calibration run would leave them
+    sg = np.float32(127.0 / 6.0)
+    xd = dev(x)
+    xq = torch.empty((M, H), dtype=torch.int8, device="cuda")
+    q8.q8_quantize(xd, scalar(float(sx)), xq)
+    np.testing.assert_array_equal(host(xq), O.quantize(x, sx))
+    # FFN1: fp32 (GELU) reference run on the GPU, then the fused int8 run
+    g32 = torch.empty((M, F), device="cuda")
+    gq = torch.empty((M, F), dtype=torch.int8, device="cuda")
+    q8.q8_linear(xq, dev(w1q), dev(b1), scalar(float(sx)), scalar(float(s1)), g32, flags=q8.EPI_GELU)
+    q8.q8_linear(xq, dev(w1q), dev(b1), scalar(float(sx)), scalar(float(s1)), gq, next_scale=scalar(float(sg)),
+                 flags=q8.EPI_GELU | q8.EPI_REQUANT)
+    ref1 = O.linear(x, w1q, s1, b1, sx=sx, act_gelu=True, threads=8)
+    assert_rel(host(g32), ref1["y"], rtol=GELU_RTOL, atol=GELU_ATOL)
+    np.testing.assert_array_equal(host(gq), O.quantize(host(g32), sg))      # codes of the GPU's own fp32 values
+    assert np.abs(host(gq).astype(np.int32) - O.quantize(ref1["y"], sg).astype(np.int32)).max() <= 1
+    assert np.abs(host(gq)).max() == 127                                     # the stored scale saturates the tail
+    # FFN2 straight from the int8 codes
+    y = torch.empty((M, H), device="cuda")
+    acc = torch.empty((M, H), dtype=torch.int32, device="cuda")
+    q8.q8_linear(gq, dev(w2q), dev(b2), scalar(float(sg)), scalar(float(s2)), y, acc_out=acc)
+    bq2 = O.quantize_bias(b2, H, sg, [s2])
+    acc_ref = O.gemm_i8(host(gq), w2q, bq2, threads=8)
+    np.testing.assert_array_equal(host(acc), acc_ref)
+    assert_rel(host(y), O.dequant(acc_ref, sg, [s2]))
+    # and the chain approximates the fp64 FFN it stands for
+    ref = O.gelu((x.astype(np.float64) @ W1.T.astype(np.float64) + b1).astype(np.float32)).astype(np.float64) \
+        @ W2.T.astype(np.float64) + b2
+    err = host(y).astype(np.float64) - ref
+    assert np.sqrt(np.mean(err ** 2)) < 0.05 * np.sqrt(np.mean(ref ** 2))
+
+
 def test_linear_f32_one_call_equals_chain(q8):
     d = synth.fc_layer(47, 260, 384, 300)
     r = run_linear(q8, d["x"], d["W"], d["b"])
