@@ -321,7 +321,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const int8_t* 
                     else
                         lds_dma16_run<l - A_LOADS>(qb2.rsrc, b_off[l - A_LOADS], qb2.koff, qb2.dst);
                 });
-                static_for<(NR * idx) / NM, (NR * (idx + 1)) / NM>([&](auto rc) {
+                // first fragments of stage kt+1: early in the k-step, so they are back before its end
+                static_for<2 * idx, (2 * idx + 2 < NR ? 2 * idx + 2 : NR)>([&](auto rc) {
                     constexpr int r = decltype(rc)::value;
                     if constexpr (r < FM)
                         fa[0][r] = *reinterpret_cast<const v4i*>(nxt_a + a_frag_off[r][0]);
