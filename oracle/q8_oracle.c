@@ -21,7 +21,10 @@
  * an independent float64 NumPy formulation of Eq. 1, exact int64 NumPy matmul,
  * Python-integer brute force on tiny shapes, int32-exactness stress values,
  * a closed form for constant tensors, and the deterministic half-step error
- * bound against the dense fp64 product.  Unpinned: nothing in this file.
+ * bound against the dense fp64 product; for the training-side operations hand
+ * values, the grid/half-step properties of fake quantization and closed forms of
+ * the moving average.  Parity unpinned: the decay and start value of the moving
+ * average under Eq. 4 (the paper prints neither; they are arguments).
  *
  * Build: gcc -O2 -std=c11 -ffp-contract=off -fopenmp -shared -fPIC
  */
@@ -195,4 +198,49 @@ int q8o_embedding_sum3(const int8_t *word, int64_t Vw, float sw_,
         }
     }
     return Q8O_OK;
+}
+
+/* ---- training-side operations (Section 2.2; Eq. 4; Eq. 5) ------------------------------ */
+
+/* Fake quantization (Section 2.2): the value is quantized with Eq. 1 and taken straight back
+ * to floating point, x^q = Quantize(x | S, 127) / S, so that the fp32 tensor carries the
+ * rounding error of the int8 code.  One binary32 division per element. */
+int q8o_fake_quantize(const float *x, int64_t n, float scale, float *xq)
+{
+    const float m = (float)top_value(8);
+    if (!isfinite(scale) || scale == 0.0f) return Q8O_ERR_NONFINITE;
+    for (int64_t i = 0; i < n; ++i) {
+        if (!isfinite(x[i])) return Q8O_ERR_NONFINITE;
+        float p = x[i] * scale;
+        float r = round_half_away(p);
+        r = fminf(fmaxf(r, -m), m);
+        xq[i] = r / scale;
+    }
+    return Q8O_OK;
+}
+
+/* The running statistic under Eq. 4: an exponential moving average of max|x| over the
+ * batches seen in training.  The paper prints neither the decay nor the start value; both are
+ * arguments here (the first batch starts the average at its own max|x|):
+ *     ema <- decay * ema + (1 - decay) * amax,
+ * four binary32 operations, each rounded, in exactly this order. */
+int q8o_ema_update(float ema_prev, int initialized, float amax, float decay, float *ema_out)
+{
+    if (!isfinite(amax) || !isfinite(ema_prev) || !(decay >= 0.0f && decay <= 1.0f)) return Q8O_ERR_NONFINITE;
+    if (!initialized) {
+        *ema_out = amax;
+        return Q8O_OK;
+    }
+    float keep = decay * ema_prev;
+    float w = 1.0f - decay;
+    float take = w * amax;
+    *ema_out = keep + take;
+    return Q8O_OK;
+}
+
+/* Eq. 5, the straight-through estimator: the derivative of the fake-quantized value with
+ * respect to its input is a vector of ones, so the gradient passes unchanged. */
+void q8o_ste_backward(const float *grad_xq, int64_t n, float *grad_x)
+{
+    for (int64_t i = 0; i < n; ++i) grad_x[i] = grad_xq[i] * 1.0f;
 }

@@ -158,6 +158,31 @@ def embedding_sum3(word_q, s_word, pos_q, s_pos, typ_q, s_typ, wid, pid, tid) ->
     return out
 
 
+
+def fake_quantize(x, s) -> np.ndarray:
+    """x^q = Quantize(x | S, 127) / S in fp32 (Section 2.2)."""
+    x = _f32(x)
+    y = np.empty(x.shape, dtype=np.float32)
+    _check(lib().q8o_fake_quantize(_p(x, C.c_float), C.c_int64(x.size), C.c_float(float(s)), _p(y, C.c_float)),
+           "fake_quantize")
+    return y
+
+
+def ema_update(ema_prev, initialized: bool, amax, decay) -> np.float32:
+    """One step of the moving average of max|x| under Eq. 4."""
+    out = C.c_float()
+    _check(lib().q8o_ema_update(C.c_float(float(ema_prev)), C.c_int(1 if initialized else 0), C.c_float(float(amax)),
+                                C.c_float(float(decay)), C.byref(out)), "ema_update")
+    return np.float32(out.value)
+
+
+def ste_backward(grad_xq) -> np.ndarray:
+    """Eq. 5: the gradient passes the fake quantization unchanged."""
+    g = _f32(grad_xq)
+    out = np.empty(g.shape, dtype=np.float32)
+    lib().q8o_ste_backward(_p(g, C.c_float), C.c_int64(g.size), _p(out, C.c_float))
+    return out
+
 def quantize_tensor(x):
     """Dynamic per-tensor quantization: S = 127 / max|x| (Eq. 3), then Eq. 1."""
     s = scale(absmax(x))

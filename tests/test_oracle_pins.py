@@ -285,3 +285,72 @@ def test_embedding_sum3_matches_fp64_sum():
     out = O.embedding_sum3(qs[0][0], qs[0][1], qs[1][0], qs[1][1], qs[2][0], qs[2][1], *ids)
     ref = sum(q[i].astype(np.float64) / float(s) for (q, s), i in zip(qs, ids))
     np.testing.assert_allclose(out, ref, rtol=1e-6, atol=1e-9)
+
+
+# ---------------------------------------------------------------- Section 2.2, Eq. 4, Eq. 5 (training side)
+def test_fake_quantize_hand_cases(golden_dir):
+    from fractions import Fraction
+    for c in _load(golden_dir, "training_cases.json")["fake_quantize"]:
+        x = np.array(c["x"], dtype=np.float32)
+        y = O.fake_quantize(x, c["scale"])
+        assert y.dtype == np.float32
+        if "xq" in c:
+            assert y.tolist() == c["xq"], c["name"]
+        else:  # exact rational code / S, correctly rounded to binary32
+            for v, code in zip(y.tolist(), c["codes"]):
+                exact = Fraction(code) / Fraction(c["scale"])
+                half_ulp = Fraction(float(np.spacing(np.float32(abs(v))))) / 2
+                assert abs(Fraction(v) - exact) <= half_ulp, (c["name"], code)
+
+
+def test_fake_quantize_properties():
+    g = synth.rng(77)
+    x = synth.activations(g, 257, 96)
+    s = O.scale(O.absmax(x))
+    y = O.fake_quantize(x, s)
+    # every value sits on the grid {k / S, |k| <= 127}, and the code read back is Eq. 1's
+    k = np.rint(y.astype(np.float64) * float(s))
+    assert np.abs(k).max() == 127
+    np.testing.assert_array_equal(k.astype(np.int8), O.quantize(x, s))
+    assert np.abs(y.astype(np.float64) - k / float(s)).max() <= np.spacing(np.float32(np.abs(y).max())) / 2
+    # half-step error bound of rounding to nearest inside the clamp range
+    step = 1.0 / float(s)
+    assert np.abs(y.astype(np.float64) - x.astype(np.float64)).max() <= 0.5 * step * (1 + 1e-6)
+    # odd symmetry, idempotence, at most 255 levels
+    np.testing.assert_array_equal(O.fake_quantize(-x, s), -y)
+    np.testing.assert_array_equal(O.fake_quantize(y, s), y)
+    assert np.unique(y).size <= 255
+    # beyond the range the value saturates at +-127 / S
+    big = np.array([1e6, -1e6], dtype=np.float32)
+    sat = O.fake_quantize(big, s)
+    assert sat[0] == np.float32(127.0) / s and sat[1] == -sat[0]
+
+
+def test_ema_hand_cases_and_closed_forms(golden_dir):
+    for c in _load(golden_dir, "training_cases.json")["ema"]:
+        got = O.ema_update(c["prev"], c["initialized"], c["amax"], c["decay"])
+        assert got == np.float32(c["ema"]), c["why"]
+    # batches of max 0 after a start of a0 with decay 1/2: a0 / 2^k, exact
+    e = O.ema_update(0.0, False, 48.0, 0.5)
+    for k in range(1, 20):
+        e = O.ema_update(e, True, 0.0, 0.5)
+        assert e == np.float32(48.0 / 2 ** k)
+    # the average stays between the old value and the batch value
+    g = synth.rng(78)
+    e = np.float32(1.0)
+    for a in np.abs(g.standard_normal(200)).astype(np.float32) * 3:
+        n = O.ema_update(e, True, a, 0.9)
+        lo, hi = min(e, a), max(e, a)
+        assert lo * (1 - 1e-6) <= n <= hi * (1 + 1e-6)
+        e = n
+    # Eq. 4: the scale is 127 over the averaged max
+    assert O.scale(O.ema_update(8.0, True, 4.0, 0.75)) == np.float32(127.0) / np.float32(7.0)
+    with pytest.raises(O.OracleError):
+        O.ema_update(1.0, True, 1.0, 1.5)
+
+
+def test_ste_backward_is_identity():
+    g = synth.rng(79)
+    grad = synth.activations(g, 33, 65)
+    out = O.ste_backward(grad)
+    assert out.tobytes() == grad.tobytes()
