@@ -280,6 +280,23 @@ def main():
                                 "tokens_per_s": round(layer.M / dts, 1), "steps": n_static,
                                 "note": "stored activation scales: no abs-max passes; FFN1 emits int8 (GELU + "
                                         "requantize epilogue) straight into FFN2"}
+    # training-side quantizer (Section 2.2 / Eq. 4): abs-max, moving-average step and fake quantization
+    # of the FFN2-input-sized activation; bound by HBM (4 B read for the abs-max, 4 B + 4 B for the rest)
+    xs = layer.g
+    fq = torch.empty_like(xs)
+    ema_state = torch.zeros(2, device="cuda")
+    n_tr = max(10, args.steps // 4)
+    for _ in range(3):
+        q8.q8_fake_quantize_ema(xs, 0.9, ema_state, layer.scal, fq)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n_tr):
+        q8.q8_fake_quantize_ema(xs, 0.9, ema_state, layer.scal, fq)
+    torch.cuda.synchronize()
+    dtt = (time.perf_counter() - t0) / n_tr
+    out["training_side"] = {"op": "q8_fake_quantize_ema on fp32[%d, %d]" % tuple(xs.shape), "us_per_call": round(dtt * 1e6, 1),
+                            "algorithmic_GBps": round(12.0 * xs.numel() / dtt / 1e9, 1), "bound": "hbm",
+                            "frac_of_8TBps": round(12.0 * xs.numel() / dtt / 8e12, 3)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(d, args.cpu_sample_tokens)
     print(json.dumps(out))

@@ -155,6 +155,52 @@ q8_status q8_embedding_sum3(const int8_t* word, int64_t Vw, const int8_t* pos, i
                             const int32_t* wid, const int32_t* pid, const int32_t* tid, int64_t T,
                             float* out, int32_t* err_flag, void* stream);
 
+/*
+ * ---- training side (quantization-aware training, Section 2.2) ----
+ *
+ * Fake quantization: xq[i] = Quantize(x[i] | scale[0], 127) / scale[0], the int8 code of
+ * Eq. 1 taken straight back to fp32 (one binary32 division), so that the tensor carries the
+ * rounding error of the code.  The quantized Embedding layer in training is q8_embedding with
+ * fp32 output: its rows are already fake quantized values.
+ *   x fp32[n]; scale fp32[1] on the device; xq fp32[n], may be x itself (in place); n >= 0.
+ */
+q8_status q8_fake_quantize(const float* x, int64_t n, const float* scale, float* xq, void* stream);
+
+/*
+ * One step of the exponential moving average of max|x| that Eq. 4 divides M by.
+ *   amax[0..n_amax): abs-max values whose maximum a is this batch's max|x| (n_amax >= 1).
+ *   decay: host float in [0, 1].  The paper prints neither the decay nor the start value:
+ *   the first update (state[1] == 0) starts the average at a.
+ *   state fp32[2], kept by the caller between steps and zeroed before the first:
+ *     state[0] <- a                                   on the first update,
+ *                 decay*state[0] + (1 - decay)*a      afterwards (each operation rounded to
+ *                 binary32: the two products, the difference and the sum, in that order);
+ *     state[1] <- 1.
+ *   scale_out fp32[1] or NULL: 127 / state[0] (1.0 if the average is 0), Eq. 4.
+ *   amax_out fp32[1] or NULL: a.  Neither may overlap amax[0..n_amax) or state.
+ */
+q8_status q8_ema_update(const float* amax, int n_amax, float decay, float* state, float* amax_out,
+                        float* scale_out, void* stream);
+
+/*
+ * The activation quantizer of a training step in one call: abs-max of x, the moving-average
+ * step above, then fake quantization with the updated scale (Eq. 4 with the average that
+ * already includes this batch).  With decay = 0 the average is this tensor's own max|x|, which
+ * is the weights' quantizer in training (Eq. 3).
+ *   x fp32[n]; xq fp32[n], may be x; state as in q8_ema_update;
+ *   scal_work fp32[Q8_SCAL_WORK]: caller-provided scratch; on return scal_work[0] = max|x|,
+ *   scal_work[1] = the scale used.  n >= 0 (n = 0 counts as a batch whose max is 0).
+ */
+q8_status q8_fake_quantize_ema(const float* x, int64_t n, float decay, float* state, float* scal_work,
+                               float* xq, void* stream);
+
+/*
+ * Eq. 5, the straight-through estimator: d xq / d x is a vector of ones, so
+ * grad_x[i] = grad_xq[i].  grad_x may be grad_xq itself (then nothing is launched);
+ * otherwise the two must not overlap.  n >= 0.
+ */
+q8_status q8_ste_backward(const float* grad_xq, int64_t n, float* grad_x, void* stream);
+
 /* Library version string and a short text for a status code (host pointers, static storage). */
 const char* q8_version(void);
 const char* q8_status_str(q8_status s);

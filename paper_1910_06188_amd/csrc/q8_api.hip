@@ -152,6 +152,53 @@ q8_status q8_embedding_sum3(const int8_t* word, int64_t Vw, const int8_t* pos, i
                : Q8_OK;
 }
 
+q8_status q8_fake_quantize(const float* x, int64_t n, const float* scale, float* xq, void* stream)
+{
+    if (n < 0) return Q8_ERR_SHAPE;
+    if (n == 0) return Q8_OK;
+    if (!x || !scale || !xq) return Q8_ERR_NULL;
+    if (misaligned(x, 4) || misaligned(scale, 4) || misaligned(xq, 4)) return Q8_ERR_ALIGN;
+    return q8::launch_fake_quantize(x, n, scale, xq, as_stream(stream)) ? Q8_ERR_LAUNCH : Q8_OK;
+}
+
+q8_status q8_ema_update(const float* amax, int n_amax, float decay, float* state, float* amax_out, float* scale_out,
+                        void* stream)
+{
+    if (n_amax < 1 || !(decay >= 0.0f && decay <= 1.0f)) return Q8_ERR_SHAPE;
+    if (!amax || !state) return Q8_ERR_NULL;
+    if (misaligned(amax, 4) || misaligned(state, 4) || misaligned(amax_out, 4) || misaligned(scale_out, 4))
+        return Q8_ERR_ALIGN;
+    return q8::launch_ema_update(amax, n_amax, decay, state, amax_out, scale_out, as_stream(stream)) ? Q8_ERR_LAUNCH
+                                                                                                      : Q8_OK;
+}
+
+q8_status q8_fake_quantize_ema(const float* x, int64_t n, float decay, float* state, float* scal_work, float* xq,
+                               void* stream)
+{
+    if (n < 0 || !(decay >= 0.0f && decay <= 1.0f)) return Q8_ERR_SHAPE;
+    if (!state || !scal_work) return Q8_ERR_NULL;
+    if (n > 0 && (!x || !xq)) return Q8_ERR_NULL;
+    if (misaligned(x, 4) || misaligned(xq, 4) || misaligned(state, 4) || misaligned(scal_work, 4)) return Q8_ERR_ALIGN;
+    int slots = 1;
+    if (n == 0) {
+        if (q8::launch_absmax(x, 0, scal_work + 2, nullptr, as_stream(stream))) return Q8_ERR_LAUNCH;
+    } else if (q8::launch_absmax_partial(x, n, scal_work + 2, &slots, as_stream(stream))) {
+        return Q8_ERR_LAUNCH;
+    }
+    if (q8::launch_ema_update(scal_work + 2, slots, decay, state, scal_work, scal_work + 1, as_stream(stream)))
+        return Q8_ERR_LAUNCH;
+    return q8::launch_fake_quantize(x, n, scal_work + 1, xq, as_stream(stream)) ? Q8_ERR_LAUNCH : Q8_OK;
+}
+
+q8_status q8_ste_backward(const float* grad_xq, int64_t n, float* grad_x, void* stream)
+{
+    if (n < 0) return Q8_ERR_SHAPE;
+    if (n == 0) return Q8_OK;
+    if (!grad_xq || !grad_x) return Q8_ERR_NULL;
+    if (misaligned(grad_xq, 4) || misaligned(grad_x, 4)) return Q8_ERR_ALIGN;
+    return q8::launch_ste_backward(grad_xq, n, grad_x, as_stream(stream)) ? Q8_ERR_LAUNCH : Q8_OK;
+}
+
 const char* q8_version(void) { return "q8 0.1.0 (gfx950)"; }
 
 const char* q8_status_str(q8_status s)

@@ -1,6 +1,8 @@
-// Abs-max / scale (Eq. 3, Section 4.1) and quantize (Eq. 1) kernels for gfx950.
-// Both are single passes over fp32 data and are bound by HBM bandwidth:
-// abs-max reads 4 B per element, quantize reads 4 B and writes 1 B.
+// Abs-max / scale (Eq. 3, Section 4.1) and quantize (Eq. 1) kernels for gfx950, and the
+// training-side twins: fake quantization (Section 2.2), the moving average of max|x| under
+// Eq. 4 and the straight-through gradient (Eq. 5).  All are single passes over fp32 data and
+// are bound by HBM bandwidth: abs-max reads 4 B per element, quantize reads 4 B and writes
+// 1 B, fake quantization and the gradient copy read 4 B and write 4 B.
 #include "q8_device.h"
 #include "q8_launch.h"
 
@@ -186,6 +188,106 @@ __global__ __launch_bounds__(kEwThreads) void quantize_scalar_kernel(const float
         q[i] = (int8_t)quantize_code(x[i], s);
 }
 
+// ---- training side ---------------------------------------------------------------------
+
+// Section 2.2: Quantize(x | S, 127) / S, the code taken straight back to fp32 with one
+// correctly rounded binary32 division.
+__device__ __forceinline__ float fake_quantize_value(float x, float s)
+{
+    float r = round_half_away(__fmul_rn(x, s));
+    r = __builtin_fminf(__builtin_fmaxf(r, -127.0f), 127.0f);
+    return __fdiv_rn(r, s);
+}
+
+__device__ __forceinline__ float4 fake_quantize4(float4 v, float s)
+{
+    return make_float4(fake_quantize_value(v.x, s), fake_quantize_value(v.y, s), fake_quantize_value(v.z, s),
+                       fake_quantize_value(v.w, s));
+}
+
+// x and xq 16-byte aligned (they may be the same buffer: every element is read before its
+// own store and by no other thread).
+template <bool kVec>
+__global__ __launch_bounds__(kEwThreads) void fake_quantize_kernel(const float* x, int64_t n,
+                                                                    const float* __restrict__ scale, float* xq)
+{
+    const float s = scale[0];
+    const int64_t stride = (int64_t)gridDim.x * kEwThreads;
+    int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x;
+    if (kVec) {
+        const float4* xv = reinterpret_cast<const float4*>(x);
+        float4* yv = reinterpret_cast<float4*>(xq);
+        const int64_t nvec = n >> 2;
+        for (; i + (kEwUnroll - 1) * stride < nvec; i += kEwUnroll * stride) {
+            float4 v[kEwUnroll];
+#pragma unroll
+            for (int u = 0; u < kEwUnroll; ++u) v[u] = xv[i + u * stride];
+#pragma unroll
+            for (int u = 0; u < kEwUnroll; ++u) yv[i + u * stride] = fake_quantize4(v[u], s);
+        }
+        for (; i < nvec; i += stride) yv[i] = fake_quantize4(xv[i], s);
+        if (blockIdx.x == 0) {
+            int64_t t = (nvec << 2) + threadIdx.x;
+            if (t < n) xq[t] = fake_quantize_value(x[t], s);
+        }
+    } else {
+        for (; i < n; i += stride) xq[i] = fake_quantize_value(x[i], s);
+    }
+}
+
+// One step of the moving average under Eq. 4 (one workgroup): a = max of the n_amax values,
+// state[0] <- a on the first call (state[1] == 0), else decay * state[0] + (1 - decay) * a,
+// four binary32 operations in this order; state[1] <- 1; the scale is 127 over the average.
+__global__ __launch_bounds__(kEwThreads) void ema_update_kernel(const float* __restrict__ amax, int n_amax,
+                                                                 float decay, float* state, float* amax_out,
+                                                                 float* scale_out)
+{
+    unsigned m = 0u;
+    for (int i = threadIdx.x; i < n_amax; i += kEwThreads) m = max(m, abs_bits(amax[i]));
+    m = block_max_u32(m);
+    if (threadIdx.x == 0) {
+        const float a = __uint_as_float(m);
+        float e = a;
+        if (state[1] != 0.0f) {
+            const float keep = __fmul_rn(decay, state[0]);
+            const float take = __fmul_rn(__fsub_rn(1.0f, decay), a);
+            e = __fadd_rn(keep, take);
+        }
+        state[0] = e;
+        state[1] = 1.0f;
+        if (amax_out) amax_out[0] = a;
+        if (scale_out) scale_out[0] = scale_from_amax(e);
+    }
+}
+
+// Eq. 5: the gradient passes unchanged.  A plain streaming copy.
+template <bool kVec>
+__global__ __launch_bounds__(kEwThreads) void ste_backward_kernel(const float* __restrict__ g, int64_t n,
+                                                                   float* __restrict__ gx)
+{
+    const int64_t stride = (int64_t)gridDim.x * kEwThreads;
+    int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x;
+    if (kVec) {
+        const float4* gv = reinterpret_cast<const float4*>(g);
+        float4* ov = reinterpret_cast<float4*>(gx);
+        const int64_t nvec = n >> 2;
+        for (; i + (kEwUnroll - 1) * stride < nvec; i += kEwUnroll * stride) {
+            float4 v[kEwUnroll];
+#pragma unroll
+            for (int u = 0; u < kEwUnroll; ++u) v[u] = gv[i + u * stride];
+#pragma unroll
+            for (int u = 0; u < kEwUnroll; ++u) ov[i + u * stride] = v[u];
+        }
+        for (; i < nvec; i += stride) ov[i] = gv[i];
+        if (blockIdx.x == 0) {
+            int64_t t = (nvec << 2) + threadIdx.x;
+            if (t < n) gx[t] = g[t];
+        }
+    } else {
+        for (; i < n; i += stride) gx[i] = g[i];
+    }
+}
+
 static int am_grid(int64_t nvec)
 {
     int64_t per_block = (int64_t)kEwThreads * 6;  // 6 to 8 vectors per thread in one trip
@@ -260,6 +362,36 @@ int launch_quantize(const float* x, int64_t n, const float* scale, int8_t* q, hi
         hipLaunchKernelGGL(quantize_vec_kernel, dim3(ew_grid(n >> 2)), dim3(kEwThreads), 0, st, x, n, scale, q);
     else
         hipLaunchKernelGGL(quantize_scalar_kernel, dim3(ew_grid(n)), dim3(kEwThreads), 0, st, x, n, scale, q);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+int launch_fake_quantize(const float* x, int64_t n, const float* scale, float* xq, hipStream_t st)
+{
+    if (n == 0) return 0;
+    bool vec = ((reinterpret_cast<uintptr_t>(x) & 15) == 0) && ((reinterpret_cast<uintptr_t>(xq) & 15) == 0);
+    if (vec)
+        hipLaunchKernelGGL(fake_quantize_kernel<true>, dim3(ew_grid(n >> 2)), dim3(kEwThreads), 0, st, x, n, scale, xq);
+    else
+        hipLaunchKernelGGL(fake_quantize_kernel<false>, dim3(ew_grid(n)), dim3(kEwThreads), 0, st, x, n, scale, xq);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+int launch_ema_update(const float* amax, int n_amax, float decay, float* state, float* amax_out, float* scale_out,
+                      hipStream_t st)
+{
+    hipLaunchKernelGGL(ema_update_kernel, dim3(1), dim3(kEwThreads), 0, st, amax, n_amax, decay, state, amax_out,
+                       scale_out);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+int launch_ste_backward(const float* g, int64_t n, float* gx, hipStream_t st)
+{
+    if (n == 0 || g == gx) return 0;
+    bool vec = ((reinterpret_cast<uintptr_t>(g) & 15) == 0) && ((reinterpret_cast<uintptr_t>(gx) & 15) == 0);
+    if (vec)
+        hipLaunchKernelGGL(ste_backward_kernel<true>, dim3(ew_grid(n >> 2)), dim3(kEwThreads), 0, st, g, n, gx);
+    else
+        hipLaunchKernelGGL(ste_backward_kernel<false>, dim3(ew_grid(n)), dim3(kEwThreads), 0, st, g, n, gx);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 

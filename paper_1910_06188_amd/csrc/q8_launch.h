@@ -30,6 +30,12 @@ int launch_quantize_amax(const float* x, int64_t n, const float* amax, int n_ama
 int launch_scale_from_amax(const float* amax, float* scale_out, hipStream_t st);
 int launch_quantize(const float* x, int64_t n, const float* scale, int8_t* q, hipStream_t st);
 
+// Training side: fake quantization (Section 2.2), moving average of max|x| (Eq. 4), gradient copy (Eq. 5).
+int launch_fake_quantize(const float* x, int64_t n, const float* scale, float* xq, hipStream_t st);
+int launch_ema_update(const float* amax, int n_amax, float decay, float* state, float* amax_out, float* scale_out,
+                      hipStream_t st);
+int launch_ste_backward(const float* g, int64_t n, float* gx, hipStream_t st);
+
 // True when the MFMA kernel can take the problem (K % 128 == 0, K >= 128, 16-byte
 // aligned operands, each operand below 2^32 bytes).
 bool gemm_mfma_eligible(const int8_t* xq, const int8_t* wq, int64_t M, int64_t N, int64_t K);

@@ -37,7 +37,12 @@ _lib.q8_linear.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i64, _i64, _i64, _vp,
 _lib.q8_linear_f32.argtypes = [_vp, _vp, _vp, _vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _u32, _vp]
 _lib.q8_embedding.argtypes = [_vp, _vp, _i64, _i64, _vp, _i64, _vp, _i32, _vp, _vp]
 _lib.q8_embedding_sum3.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _vp]
-for _f in ("q8_absmax", "q8_scale_from_amax", "q8_quantize", "q8_quantize_amax", "q8_linear", "q8_linear_f32", "q8_embedding",
+_f32 = C.c_float
+_lib.q8_fake_quantize.argtypes = [_vp, _i64, _vp, _vp, _vp]
+_lib.q8_ema_update.argtypes = [_vp, _i32, _f32, _vp, _vp, _vp, _vp]
+_lib.q8_fake_quantize_ema.argtypes = [_vp, _i64, _f32, _vp, _vp, _vp, _vp]
+_lib.q8_ste_backward.argtypes = [_vp, _i64, _vp, _vp]
+for _f in ("q8_fake_quantize", "q8_ema_update", "q8_fake_quantize_ema", "q8_ste_backward", "q8_absmax", "q8_scale_from_amax", "q8_quantize", "q8_quantize_amax", "q8_linear", "q8_linear_f32", "q8_embedding",
            "q8_embedding_sum3"):
     getattr(_lib, _f).restype = C.c_int
 _lib.q8_version.restype = C.c_char_p
@@ -155,6 +160,36 @@ def q8_embedding_sum3(word, pos, typ, scales, wid, pid, tid, out, err_flag=None,
     _ck(_lib.q8_embedding_sum3(_ptr(word), word.shape[0], _ptr(pos), pos.shape[0], _ptr(typ), typ.shape[0],
                                _ptr(scales), H, _ptr(wid), _ptr(pid), _ptr(tid), T, _ptr(out), _ptr(err_flag),
                                _stream(stream)), "q8_embedding_sum3")
+
+
+def q8_fake_quantize(x, scale, xq, stream=None) -> None:
+    """xq = Quantize(x | S, 127) / S in fp32 (Section 2.2); xq may be x."""
+    if xq.numel() != x.numel():
+        raise ValueError("q8_fake_quantize: xq and x differ in size")
+    _ck(_lib.q8_fake_quantize(_ptr(x), x.numel(), _ptr(scale), _ptr(xq), _stream(stream)), "q8_fake_quantize")
+
+
+def q8_ema_update(amax, decay, state, amax_out=None, scale_out=None, stream=None) -> None:
+    """One step of the moving average of max|x| under Eq. 4; state = [average, started]."""
+    if state.numel() < 2:
+        raise ValueError("q8_ema_update: state holds two floats")
+    _ck(_lib.q8_ema_update(_ptr(amax), amax.numel(), float(decay), _ptr(state), _ptr(amax_out), _ptr(scale_out),
+                           _stream(stream)), "q8_ema_update")
+
+
+def q8_fake_quantize_ema(x, decay, state, scal_work, xq, stream=None) -> None:
+    """abs-max, moving-average step, fake quantization with the updated scale, in one call."""
+    if xq.numel() != x.numel() or state.numel() < 2 or scal_work.numel() < SCAL_WORK:
+        raise ValueError("q8_fake_quantize_ema: shape mismatch")
+    _ck(_lib.q8_fake_quantize_ema(_ptr(x), x.numel(), float(decay), _ptr(state), _ptr(scal_work), _ptr(xq),
+                                  _stream(stream)), "q8_fake_quantize_ema")
+
+
+def q8_ste_backward(grad_xq, grad_x, stream=None) -> None:
+    """Eq. 5: grad_x = grad_xq."""
+    if grad_x.numel() != grad_xq.numel():
+        raise ValueError("q8_ste_backward: sizes differ")
+    _ck(_lib.q8_ste_backward(_ptr(grad_xq), grad_xq.numel(), _ptr(grad_x), _stream(stream)), "q8_ste_backward")
 
 
 def raw():

@@ -71,6 +71,24 @@ def test_host_side_argument_checks(lib):
     assert lib.q8_embedding(p, p, 10, 8, None, 4, p, 0, None, None) == NULL
     assert lib.q8_embedding(p, p, 10, 8, p, 0, p, 0, None, None) == OK                       # T = 0
     assert lib.q8_embedding(p, p, -1, 8, p, 4, p, 0, None, None) == SHAPE
+    # training side: every check below returns before anything would be launched
+    lib.q8_fake_quantize.argtypes = [vp, i64, vp, vp, vp]
+    lib.q8_ema_update.argtypes = [vp, C.c_int, C.c_float, vp, vp, vp, vp]
+    lib.q8_fake_quantize_ema.argtypes = [vp, i64, C.c_float, vp, vp, vp, vp]
+    lib.q8_ste_backward.argtypes = [vp, i64, vp, vp]
+    assert lib.q8_fake_quantize(p, -1, p, p, None) == SHAPE
+    assert lib.q8_fake_quantize(p, 0, None, None, None) == OK
+    assert lib.q8_fake_quantize(p, 4, None, p, None) == NULL
+    assert lib.q8_fake_quantize(p, 4, p, p + 1, None) == ALIGN
+    assert lib.q8_ema_update(p, 0, 0.5, p, None, None, None) == SHAPE
+    assert lib.q8_ema_update(p, 1, 1.5, p, None, None, None) == SHAPE
+    assert lib.q8_ema_update(p, 1, float("nan"), p, None, None, None) == SHAPE
+    assert lib.q8_ema_update(p, 1, 0.5, None, None, None, None) == NULL
+    assert lib.q8_fake_quantize_ema(p, 8, 0.5, p, None, p, None) == NULL
+    assert lib.q8_fake_quantize_ema(p, 8, -0.1, p, p, p, None) == SHAPE
+    assert lib.q8_ste_backward(p, 8, None, None) == NULL
+    assert lib.q8_ste_backward(p, -2, p, None) == SHAPE
+    assert lib.q8_ste_backward(p, 0, None, None) == OK
 
 
 def test_product_package_does_not_reach_the_oracle():
