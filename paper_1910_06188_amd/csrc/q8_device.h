@@ -53,23 +53,25 @@ __device__ __forceinline__ float dequant_factor(float sx, float sw)
 }
 
 // GELU(v) = v * Phi(v), Phi the standard normal CDF (exact-erf GELU, kept in fp32:
-// Section 3).  Written through erfc so that the negative tail does not cancel:
-//   v <  0 : 0.5 v erfc(|v|/sqrt 2)          v >= 0 : v - 0.5 v erfc(v/sqrt 2)
+// Section 3).  Written through erfc so that the negative tail does not cancel: with
+// g = 0.5 |v| erfc(|v|/sqrt 2) >= 0,
+//   v <  0 : GELU = -g          v >= 0 : GELU = v - g          i.e. GELU = max(v, 0) - g.
 // erfc(z) = t (a1 + t (a2 + t (a3 + t (a4 + t a5)))) exp(-z^2), t = 1/(1 + p z), is the
 // classical 5-term rational fit (Abramowitz & Stegun 7.1.26, |error| <= 1.5e-7, about one
-// fp32 ulp of 1.0).  A dozen VALU operations and two transcendentals per element keep the
-// fused epilogue below the time its fp32 stores take.
+// fp32 ulp of 1.0).  The factors 0.5, 1/sqrt 2 and log2 e are folded into the constants:
+// 13 VALU operations and two transcendentals per element.  In the fused GEMM epilogue this
+// arithmetic, not the store, is what the GELU variants wait for.
 __device__ __forceinline__ float gelu_erf(float v)
 {
-    const float z = __builtin_fabsf(v) * 0.70710678118654752440f;
-    const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.3275911f, z, 1.0f));
-    const float e = __builtin_amdgcn_exp2f(-(z * z) * 1.44269504088896340736f);
-    float p = __builtin_fmaf(1.061405429f, t, -1.453152027f);
-    p = __builtin_fmaf(p, t, 1.421413741f);
-    p = __builtin_fmaf(p, t, -0.284496736f);
-    p = __builtin_fmaf(p, t, 0.254829592f);
-    const float h = 0.5f * v * (p * t * e);
-    return v >= 0.0f ? v - h : h;
+    const float a = __builtin_fabsf(v);
+    const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.3275911f * 0.70710678118654752440f, a, 1.0f));
+    const float e = __builtin_amdgcn_exp2f((v * v) * (-0.5f * 1.44269504088896340736f));
+    float p = __builtin_fmaf(0.5f * 1.061405429f, t, 0.5f * -1.453152027f);
+    p = __builtin_fmaf(p, t, 0.5f * 1.421413741f);
+    p = __builtin_fmaf(p, t, 0.5f * -0.284496736f);
+    p = __builtin_fmaf(p, t, 0.5f * 0.254829592f);
+    const float g = a * ((p * t) * e);
+    return __builtin_fmaxf(v, 0.0f) - g;
 }
 
 __device__ __forceinline__ unsigned wave_max_u32(unsigned v)

@@ -78,7 +78,9 @@ __global__ __launch_bounds__(kEwThreads) void absmax_atomic_kernel(const float* 
                                                                     unsigned* amax_bits)
 {
     unsigned m = block_max_u32(absmax_thread(x, n, head));
-    if (threadIdx.x == 0) atomicMax(amax_bits, m);
+    // the maximum only grows: skip the serialising read-modify-write when there is nothing to add
+    if (threadIdx.x == 0 && m > __hip_atomic_load(amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+        atomicMax(amax_bits, m);
 }
 
 // Fused path: each workgroup leaves its abs-max in its own slot; the quantize kernel that

@@ -25,6 +25,8 @@ int launch_tile_256x256_w4(const int8_t*, const int8_t*, int, int, int, int, con
 int launch_tile_256x256_w8(const int8_t*, const int8_t*, int, int, int, int, const Epilogue&, hipStream_t);
 int launch_tile_128x128_w4(const int8_t*, const int8_t*, int, int, int, int, const Epilogue&, hipStream_t);
 int launch_tile_192x256_w4(const int8_t*, const int8_t*, int, int, int, int, const Epilogue&, hipStream_t);
+int launch_tile_192x256_w8(const int8_t*, const int8_t*, int, int, int, int, const Epilogue&, hipStream_t);
+int launch_tile_192x128_w4(const int8_t*, const int8_t*, int, int, int, int, const Epilogue&, hipStream_t);
 
 // Any shape and alignment: one thread per output element.  Slow; same results.
 __global__ __launch_bounds__(256) void gemm_generic_kernel(const int8_t* __restrict__ X, const int8_t* __restrict__ W,
@@ -70,20 +72,38 @@ int launch_gemm_mfma(const int8_t* xq, const int8_t* wq, int64_t M64, int64_t N6
     const int M = (int)M64, N = (int)N64, K = (int)K64;
     int v = g_variant;
     if (v == 0) {
-        // Pick the tile whose launch leaves the 256 compute units least idle: large tiles
-        // once they fill the chip, else the 192-row tile if it divides the work evenly,
-        // else small tiles.
-        auto tiles = [&](int bm, int bn) { return (int64_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
-        auto idle = [&](int64_t t) { return (double)(((t + 255) / 256) * 256 - t) / (double)(((t + 255) / 256) * 256); };
-        const int64_t t256 = tiles(256, 256), t192 = tiles(192, 256);
-        if (t256 >= 256 && idle(t256) <= 0.10)
-            v = 2;
-        else if (t192 >= 192 && idle(t192) <= idle(t256))
-            v = 4;
-        else if (t256 >= 512)
-            v = 2;
-        else
-            v = 3;
+        // Pick the tile shape with the best expected use of the chip: the fraction of the launch's
+        // workgroup slots that hold work (256 compute units; tiles whose rings take half of the
+        // LDS run two workgroups per unit, one's epilogue under the other's main loop), times the
+        // fraction of each tile that lies inside y, times a prior of the shape itself.  The priors
+        // come from timing each FC of a BERT-Large layer inside the whole layer step, where the
+        // outputs of the neighbouring kernels keep the HBM busy (timings of a GEMM run alone, its
+        // operands and output warm in the caches, rank the shapes differently and do not carry
+        // over): long reductions favour the 192x256 tiles (most MFMAs per byte staged); short ones
+        // the paired tiles -- 128x128 with its three-deep w ring when the output is fp32, 192x128
+        // when the epilogue writes int8.
+        struct Cand { int variant, bm, bn, per_cu; double prior_long, prior_short_f32, prior_short_i8; };
+        static const Cand cands[] = {
+            {5, 192, 256, 1, 1.00, 0.97, 0.90}, {4, 192, 256, 1, 0.99, 0.90, 0.85}, {2, 256, 256, 1, 0.96, 0.97, 0.95},
+            {6, 192, 128, 2, 0.95, 0.93, 1.00}, {3, 128, 128, 2, 0.90, 1.00, 0.97},
+        };
+        const bool int8_out = (ep.flags & 4u) != 0;
+        double best = -1.0;
+        for (const Cand& c : cands) {
+            const int64_t tm = (M + c.bm - 1) / c.bm, tn = (N + c.bn - 1) / c.bn, tiles = tm * tn;
+            const double inside = ((double)M * N) / ((double)tiles * c.bm * c.bn);
+            // rounds of the launch: a last round that fills at most one workgroup per unit of a paired
+            // shape runs unshared and ends early
+            const int64_t slots = 256 * c.per_cu, full = tiles / slots, rem = tiles % slots;
+            const double rounds = (double)full + (rem == 0 ? 0.0 : (c.per_cu == 2 && rem <= 256) ? 0.6 : 1.0);
+            const double slots_used = ((double)tiles / (double)slots) / rounds;
+            const double prior = K >= 2048 ? c.prior_long : (int8_out ? c.prior_short_i8 : c.prior_short_f32);
+            const double score = prior * slots_used * inside;
+            if (score > best) {
+                best = score;
+                v = c.variant;
+            }
+        }
     }
     const int group_m = 8;
     switch (v) {
@@ -91,6 +111,8 @@ int launch_gemm_mfma(const int8_t* xq, const int8_t* wq, int64_t M64, int64_t N6
         case 2: return launch_tile_256x256_w8(xq, wq, M, N, K, group_m, ep, st);
         case 3: return launch_tile_128x128_w4(xq, wq, M, N, K, group_m, ep, st);
         case 4: return launch_tile_192x256_w4(xq, wq, M, N, K, group_m, ep, st);
+        case 5: return launch_tile_192x256_w8(xq, wq, M, N, K, group_m, ep, st);
+        case 6: return launch_tile_192x128_w4(xq, wq, M, N, K, group_m, ep, st);
         default: return 1;
     }
 }

@@ -132,8 +132,16 @@ __device__ __forceinline__ void static_for(F&& f)
 // Q8_EPI_ABSMAX (2) and Q8_EPI_REQUANT (4) with no accumulator dump; -1 = decide at run time
 // (any flags, optional dump).  With one wave per SIMD a per-element run-time branch costs
 // more than the arithmetic it guards, so the combinations that matter get their own kernel.
+// Waves per SIMD the kernel is compiled for: a tile whose rings take at most half of the LDS is
+// meant to run as two workgroups per compute unit (one's epilogue under the other's main loop),
+// which only happens if each wave also stays within half of the register file.
+constexpr int mfma_waves_per_simd(int BM, int BN, int SB, int NW)
+{
+    return ((2 * BM + SB * BN) * kBK <= 80 * 1024 ? 2 : 1) * (NW / 4);
+}
+
 template <int BM, int BN, int WGM, int WGN, int SB, int kEpi>
-__global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const int8_t* __restrict__ X,
+__global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM* WGN)) void gemm_mfma_kernel(const int8_t* __restrict__ X,
                                                                    const int8_t* __restrict__ W, int M, int N, int K,
                                                                    int tiles_n, int group_m, Epilogue ep)
 {
@@ -373,8 +381,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const int8_t* 
                     if (do_req)
                         __builtin_amdgcn_raw_buffer_store_b8((unsigned char)quantize_code(yv, next_scale), ry, elem0,
                                                              row_elems, 0);
-                    else
-                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(yv), ry, elem0 * 4, row_elems * 4, 0);
+                    else  // fp32 y is stored non-temporally: it is far larger than the operands, is not
+                          // read again by this kernel, and kept out of the Infinity Cache it neither evicts
+                          // the next kernels' inputs nor leaves dirty lines to drain under them (whole layer
+                          // step with stored scales 310 -> 268 us; a GEMM timed alone with a cache-resident
+                          // output does not show it)
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(yv), ry, elem0 * 4, row_elems * 4, 2);  // aux 2 = non-temporal
+                    // Keep the stores trickling out between the arithmetic of the next elements: left
+                    // alone, the scheduler gathers 32 stores into one burst during which the VALU idles.
+                    if constexpr ((e & 3) == 3) __builtin_amdgcn_sched_barrier(0);
                 });
             });
         });
@@ -419,7 +434,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const int8_t* 
             if (threadIdx.x == 0) {
 #pragma unroll
                 for (int w = 1; w < NW; ++w) amax = max(amax, wave_amax[w]);
-                atomicMax(reinterpret_cast<unsigned*>(ep.out_amax), amax);
+                // The running maximum only grows, so a workgroup whose own maximum does not exceed
+                // what is already there (read past the non-coherent L2) has nothing to add: after
+                // the first few workgroups almost none issues the read-modify-write, which
+                // serialises on one address.
+                unsigned* slot = reinterpret_cast<unsigned*>(ep.out_amax);
+                if (amax > __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(slot, amax);
             }
         }
     }

@@ -206,7 +206,7 @@ def check_linear(r, x, b, act_gelu=False, sx_static=None, threads=8):
     return ref
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6])
 def test_linear_single_fc_config(q8, variant):
     d = synth.single_fc(0)                                  # 16 x 768 -> 768
     r = run_linear(q8, d["x"], d["W"], d["b"], variant=variant)
@@ -221,6 +221,7 @@ def test_linear_single_fc_config(q8, variant):
 @pytest.mark.parametrize("M,K,N,variant", [
     (300, 256, 520, 0), (700, 384, 600, 1), (700, 384, 600, 2), (700, 384, 600, 3), (700, 384, 600, 4),
     (257, 128, 129, 1), (1, 128, 1, 3), (513, 1024, 257, 2), (255, 640, 1000, 4), (1030, 256, 2100, 1), (768, 384, 512, 4), (512, 1024, 512, 2),
+    (700, 384, 600, 5), (385, 256, 770, 5), (768, 1024, 512, 5), (700, 384, 600, 6), (385, 256, 770, 6), (768, 1024, 512, 6),
 ])
 def test_linear_mfma_ragged_multi_tile(q8, M, K, N, variant):
     d = synth.fc_layer(1000 + M + N, M, K, N)
@@ -316,7 +317,7 @@ def test_linear_random_int8_all_variants_asymmetric(q8):
     xq = synth.random_int8(g, (M, K), -128, 127)
     wq = synth.random_int8(g, (N, K), -128, 127)
     ref = O.gemm_i8(xq, wq, threads=8)
-    for variant in (1, 2, 3, 4):
+    for variant in (1, 2, 3, 4, 5, 6):
         q8.set_gemm_variant(variant)
         try:
             acc = torch.zeros((M, N), dtype=torch.int32, device="cuda")
@@ -395,7 +396,7 @@ def test_linear_specialised_epilogues(q8, M, K, N):
     wq = dev(synth.random_int8(g, (N, K)))
     b = dev(synth.bias(g, N))
     sx, sw, ns = scalar(24.0), scalar(900.0), scalar(9.0)
-    for variant in (1, 2, 3, 4):
+    for variant in (1, 2, 3, 4, 5, 6):
         q8.set_gemm_variant(variant)
         try:
             for flags in range(8):
