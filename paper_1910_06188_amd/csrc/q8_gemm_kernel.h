@@ -362,6 +362,14 @@ __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM*
         const __amdgpu_buffer_rsrc_t racc = __builtin_amdgcn_make_buffer_rsrc(
             ep.acc_out, 0, do_dump ? (int)((unsigned)M * (unsigned)N * 4u) : 0, 0x00020000);
         const int row0 = m0 + wm * TM + 4 * hi;  // first row this lane stores
+        // An fp32 y larger than a quarter of the 256 MB Infinity Cache is stored non-temporally:
+        // it could not stay cached until its consumer runs anyway, and kept out it neither evicts
+        // the next kernels' inputs nor leaves dirty lines to drain under them (whole BERT-Large
+        // layer step 5-6 % faster; a GEMM timed alone with a cache-resident output does not show
+        // it).  Smaller outputs are left for the cache to hand to their consumer.
+        const bool stream_out = (int64_t)M * N * 4 > ((int64_t)64 << 20);
+        auto store_tile = [&](auto ntc) {
+        constexpr int kAux = decltype(ntc)::value ? 2 : 0;  // aux bit 1 = nt
         static_for<0, FN>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
             const int n = n0 + wn * TN + j * 32 + l32;
@@ -381,18 +389,19 @@ __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM*
                     if (do_req)
                         __builtin_amdgcn_raw_buffer_store_b8((unsigned char)quantize_code(yv, next_scale), ry, elem0,
                                                              row_elems, 0);
-                    else  // fp32 y is stored non-temporally: it is far larger than the operands, is not
-                          // read again by this kernel, and kept out of the Infinity Cache it neither evicts
-                          // the next kernels' inputs nor leaves dirty lines to drain under them (whole layer
-                          // step with stored scales 310 -> 268 us; a GEMM timed alone with a cache-resident
-                          // output does not show it)
-                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(yv), ry, elem0 * 4, row_elems * 4, 2);  // aux 2 = non-temporal
+                    else
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(yv), ry, elem0 * 4, row_elems * 4, kAux);
                     // Keep the stores trickling out between the arithmetic of the next elements: left
                     // alone, the scheduler gathers 32 stores into one burst during which the VALU idles.
                     if constexpr ((e & 3) == 3) __builtin_amdgcn_sched_barrier(0);
                 });
             });
         });
+        };
+        if (stream_out && !do_req)
+            store_tile(std::true_type{});
+        else
+            store_tile(std::false_type{});
     } else {
         static_for<0, FN>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
