@@ -368,6 +368,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM*
         // layer step 5-6 % faster; a GEMM timed alone with a cache-resident output does not show
         // it).  Smaller outputs are left for the cache to hand to their consumer.
         const bool stream_out = (int64_t)M * N * 4 > ((int64_t)64 << 20);
+        float famax = 0.0f;
         auto store_tile = [&](auto ntc) {
         constexpr int kAux = decltype(ntc)::value ? 2 : 0;  // aux bit 1 = nt
         static_for<0, FN>([&](auto jc) {
@@ -385,7 +386,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM*
                     float yv = (float)a * cc.r;
                     if (do_dump) __builtin_amdgcn_raw_buffer_store_b32((unsigned)a, racc, elem0 * 4, row_elems * 4, 0);
                     if (do_gelu) yv = gelu_erf(yv);
-                    if (do_amax) amax = max(amax, f32_abs_bits(yv));
+                    if (do_amax) famax = __builtin_fmaxf(famax, __builtin_fabsf(yv));  // one VALU op: |.| is a source modifier
                     if (do_req)
                         __builtin_amdgcn_raw_buffer_store_b8((unsigned char)quantize_code(yv, next_scale), ry, elem0,
                                                              row_elems, 0);
@@ -402,6 +403,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM*
             store_tile(std::true_type{});
         else
             store_tile(std::false_type{});
+        amax = __float_as_uint(famax);  // non-negative floats order like their bit patterns
     } else {
         static_for<0, FN>([&](auto jc) {
             constexpr int j = decltype(jc)::value;

@@ -386,6 +386,34 @@ def test_linear_epilogue_gelu_absmax_requant(q8, M, K, N):
     np.testing.assert_array_equal(r4["y"], O.quantize(r["y"], ns2))
 
 
+def test_gelu_epilogue_dense_grid(q8):
+    """The fused GELU on a dense grid of arguments: with all-zero activations the accumulator is the
+    quantized bias, so y = bias exactly (scales 32 x 32 = 2^10, bias on the 2^-10 grid) and the
+    epilogue's GELU is seen on every multiple of 1/1024 in [-12, 12] -- both tails, the minimum near
+    -0.75 and the clamp of the fit at |v| = 6 included.  MFMA and generic kernels."""
+    import math
+    grid = (np.arange(-12 * 1024, 12 * 1024 + 1, dtype=np.float64) / 1024.0)
+    N = 24576
+    b = np.zeros(N, dtype=np.float32)
+    b[:] = grid[:N].astype(np.float32)
+    b[-1] = np.float32(1e4)                                   # far beyond the clamp
+    b[-2] = np.float32(-1e4)
+    ref = O.gelu(b)
+    for M, K in ((64, 128), (3, 100)):                        # MFMA path / generic path
+        xq = torch.zeros((M, K), dtype=torch.int8, device="cuda")
+        wq = dev(synth.random_int8(synth.rng(5), (N, K)))
+        y = torch.empty((M, N), device="cuda")
+        am = scalar(0.0)
+        q8.q8_linear(xq, wq, dev(b), scalar(32.0), scalar(32.0), y, out_amax=am, flags=q8.EPI_GELU | q8.EPI_ABSMAX)
+        got = host(y)
+        for m in (0, M - 1):
+            assert_rel(got[m], ref, rtol=GELU_RTOL, atol=GELU_ATOL)
+        assert host(am)[0] == np.abs(got).max()
+        # plain epilogue returns the grid itself
+        q8.q8_linear(xq, wq, dev(b), scalar(32.0), scalar(32.0), y)
+        np.testing.assert_array_equal(host(y)[0], b)
+
+
 @pytest.mark.parametrize("M,K,N", [(768, 256, 512), (700, 384, 600)])
 def test_linear_specialised_epilogues(q8, M, K, N):
     """Each epilogue combination has a kernel of its own when no accumulator dump is asked for;
