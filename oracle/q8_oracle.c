@@ -23,7 +23,8 @@
  * a closed form for constant tensors, and the deterministic half-step error
  * bound against the dense fp64 product; for the training-side operations hand
  * values, the grid/half-step properties of fake quantization and closed forms of
- * the moving average.  Parity unpinned: the decay and start value of the moving
+ * the moving average; for Layer Normalization a hand case, the library routine in
+ * binary64 and its invariants.  Parity unpinned: the decay and start value of the moving
  * average under Eq. 4 (the paper prints neither; they are arguments).
  *
  * Build: gcc -O2 -std=c11 -ffp-contract=off -fopenmp -shared -fPIC
@@ -243,4 +244,38 @@ int q8o_ema_update(float ema_prev, int initialized, float amax, float decay, flo
 void q8o_ste_backward(const float *grad_xq, int64_t n, float *grad_x)
 {
     for (int64_t i = 0; i < n; ++i) grad_x[i] = grad_xq[i] * 1.0f;
+}
+
+/* ---- FP32 glue around the FC layers (Section 3: Layer Normalization is kept in FP32) ------- */
+
+/* Layer Normalization over the last dimension of x[M,H], x = a (+ r when a residual is given,
+ * one binary32 addition): y = (x - mean) / sqrt(var + eps) * gamma + beta with the biased
+ * variance (1/H), as in BERT.  Statistics and the normalisation are evaluated in binary64 and
+ * the result is rounded once to binary32.  The paper only says that the operation stays in
+ * FP32; the formula is the standard one (Ba et al. 2016). */
+int q8o_layernorm(const float *a, const float *r, const float *gamma, const float *beta, double eps,
+                  int64_t M, int64_t H, float *y)
+{
+    if (M < 0 || H <= 0) return Q8O_ERR_SHAPE;
+    for (int64_t m = 0; m < M; ++m) {
+        const float *pa = a + m * H, *pr = r ? r + m * H : NULL;
+        double sum = 0.0;
+        for (int64_t h = 0; h < H; ++h) {
+            float x = pr ? pa[h] + pr[h] : pa[h];
+            if (!isfinite(x)) return Q8O_ERR_NONFINITE;
+            sum += (double)x;
+        }
+        double mean = sum / (double)H, ss = 0.0;
+        for (int64_t h = 0; h < H; ++h) {
+            float x = pr ? pa[h] + pr[h] : pa[h];
+            double d = (double)x - mean;
+            ss += d * d;
+        }
+        double rstd = 1.0 / sqrt(ss / (double)H + eps);
+        for (int64_t h = 0; h < H; ++h) {
+            float x = pr ? pa[h] + pr[h] : pa[h];
+            y[m * H + h] = (float)(((double)x - mean) * rstd * (double)gamma[h] + (double)beta[h]);
+        }
+    }
+    return Q8O_OK;
 }

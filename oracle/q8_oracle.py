@@ -183,6 +183,18 @@ def ste_backward(grad_xq) -> np.ndarray:
     lib().q8o_ste_backward(_p(g, C.c_float), C.c_int64(g.size), _p(out, C.c_float))
     return out
 
+
+def layernorm(a, gamma, beta, eps=1e-12, residual=None) -> np.ndarray:
+    """LayerNorm over the last axis of a (+ residual), fp64 inside, one rounding to fp32 (Section 3: stays FP32)."""
+    a = _f32(a)
+    M, H = a.shape
+    r = _f32(residual) if residual is not None else None
+    y = np.empty((M, H), dtype=np.float32)
+    _check(lib().q8o_layernorm(_p(a, C.c_float), _p(r, C.c_float) if r is not None else None, _p(_f32(gamma), C.c_float),
+                               _p(_f32(beta), C.c_float), C.c_double(float(eps)), C.c_int64(M), C.c_int64(H),
+                               _p(y, C.c_float)), "layernorm")
+    return y
+
 def quantize_tensor(x):
     """Dynamic per-tensor quantization: S = 127 / max|x| (Eq. 3), then Eq. 1."""
     s = scale(absmax(x))

@@ -354,3 +354,48 @@ def test_ste_backward_is_identity():
     grad = synth.activations(g, 33, 65)
     out = O.ste_backward(grad)
     assert out.tobytes() == grad.tobytes()
+
+
+# ---------------------------------------------------------------- FP32 glue: Layer Normalization (Section 3)
+def test_layernorm_hand_case_and_library():
+    # x = [1, 2, 3, 4]: mean 2.5, biased variance 1.25 -> (x - 2.5) / sqrt(1.25)
+    x = np.array([[1.0, 2.0, 3.0, 4.0]], dtype=np.float32)
+    one, zero = np.ones(4, np.float32), np.zeros(4, np.float32)
+    y = O.layernorm(x, one, zero, eps=0.0)
+    exp = np.array([-1.5, -0.5, 0.5, 1.5]) / np.sqrt(1.25)
+    np.testing.assert_allclose(y[0], exp, rtol=1e-7)
+    # scale and shift: gamma = [2, 2, 2, 2], beta = [1, 0, -1, 3]
+    y2 = O.layernorm(x, 2 * one, np.array([1, 0, -1, 3], np.float32), eps=0.0)
+    np.testing.assert_allclose(y2[0], 2 * exp + np.array([1, 0, -1, 3]), rtol=1e-7)
+    # a constant row has zero variance: with eps > 0 the output is beta
+    c = np.full((1, 8), 3.25, dtype=np.float32)
+    np.testing.assert_array_equal(O.layernorm(c, np.ones(8, np.float32), np.arange(8, dtype=np.float32), eps=1e-12)[0],
+                                  np.arange(8, dtype=np.float32))
+    # the library routine in float64 on random data, with a residual
+    import torch
+    g = synth.rng(91)
+    a = synth.activations(g, 37, 768) * np.float32(3.0) + np.float32(0.7)
+    r = synth.activations(g, 37, 768)
+    gamma = (1 + 0.1 * g.standard_normal(768)).astype(np.float32)
+    beta = (0.1 * g.standard_normal(768)).astype(np.float32)
+    s32 = (a + r).astype(np.float32)                              # the one binary32 addition
+    ref = torch.nn.functional.layer_norm(torch.from_numpy(s32.astype(np.float64)), (768,), torch.from_numpy(gamma.astype(np.float64)),
+                                         torch.from_numpy(beta.astype(np.float64)), eps=1e-12).numpy()
+    got = O.layernorm(a, gamma, beta, eps=1e-12, residual=r)
+    assert np.abs(got.astype(np.float64) - ref).max() <= np.spacing(np.float32(np.abs(ref).max()))
+
+
+def test_layernorm_invariants():
+    g = synth.rng(92)
+    x = synth.activations(g, 64, 1024) * np.float32(2.0) + np.float32(5.0)
+    one, zero = np.ones(1024, np.float32), np.zeros(1024, np.float32)
+    y = O.layernorm(x, one, zero, eps=0.0).astype(np.float64)
+    assert np.abs(y.mean(axis=1)).max() < 1e-6                    # zero mean
+    assert np.abs(y.var(axis=1) - 1).max() < 1e-5                 # unit (biased) variance
+    # invariant under x -> 4 x (exact scaling by a power of two) when eps = 0
+    np.testing.assert_array_equal(O.layernorm(x * np.float32(4), one, zero, eps=0.0), O.layernorm(x, one, zero, eps=0.0))
+    # a transposed statistic (normalising over rows instead of columns) would break this: rows are independent
+    y_perm = O.layernorm(x[::-1].copy(), one, zero, eps=0.0)
+    np.testing.assert_array_equal(y_perm[::-1], O.layernorm(x, one, zero, eps=0.0))
+    with pytest.raises(O.OracleError):
+        O.layernorm(np.array([[np.inf, 1.0]], np.float32), np.ones(2, np.float32), np.zeros(2, np.float32))
