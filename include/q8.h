@@ -47,6 +47,9 @@ typedef enum {
 /* Floats of scalar scratch q8_linear_f32 needs: abs-max, scale and up to 2048 partial maxima. */
 #define Q8_SCAL_WORK 2050
 
+/* Abs-max slots written by the fused LayerNorm entry points (fp32 each; unused slots are set to 0). */
+#define Q8_AMAX_SLOTS 2048
+
 /* q8_linear epilogue bits. */
 #define Q8_EPI_GELU 1u     /* y <- gelu(y), exact-erf form, in fp32 (GELU stays FP32: Section 3) */
 #define Q8_EPI_ABSMAX 2u   /* out_amax[0] <- max(out_amax[0], max|y|) over the fp32 outputs of this call */
@@ -200,6 +203,39 @@ q8_status q8_fake_quantize_ema(const float* x, int64_t n, float decay, float* st
  * otherwise the two must not overlap.  n >= 0.
  */
 q8_status q8_ste_backward(const float* grad_xq, int64_t n, float* grad_x, void* stream);
+
+/*
+ * ---- FP32 glue fused with the next layer's quantizer ----
+ *
+ * Layer Normalization over the last dimension (Section 3: Softmax, Layer Normalization and
+ * GELU are kept in FP32), with the residual addition in front of it and, behind it, the first
+ * half of the dynamic quantizer of the FC layer that consumes its output (Section 4.1: the
+ * abs-max of each incoming activation tensor):
+ *     x[m,:] = a[m,:] (+ residual[m,:], one binary32 addition)
+ *     y[m,h] = (x[m,h] - mean_m) / sqrt(var_m + eps) * gamma[h] + beta[h]      (biased variance)
+ *     amax_slots[0..Q8_AMAX_SLOTS) = partial maxima of |y| whose maximum is max|y|; pass them to
+ *     q8_quantize_amax(y, ..., amax_slots, Q8_AMAX_SLOTS, ...) and no abs-max pass is needed.
+ *   a fp32[M,H]; residual fp32[M,H] or NULL; gamma, beta fp32[H]; eps host float (BERT: 1e-12).
+ *   y fp32[M,H], may be a itself (in place); amax_slots fp32[Q8_AMAX_SLOTS] or NULL.
+ *   Statistics and normalisation are evaluated in binary64 and rounded once: y is within one
+ *   ulp of the exact value.  M >= 0 (M = 0: every slot 0); H >= 1.  Rows with H % 4 == 0,
+ *   H <= 2048 and 16-byte aligned pointers stay in registers; others take a slower kernel with
+ *   the same results.
+ */
+q8_status q8_layernorm_absmax(const float* a, const float* residual, const float* gamma, const float* beta,
+                              float eps, int64_t M, int64_t H, float* y, float* amax_slots, void* stream);
+
+/*
+ * BERT's input block in one pass: the three-table int8 embedding lookup of q8_embedding_sum3
+ * (Section 3), Layer Normalization of the summed rows, and the abs-max slots of the result as
+ * above.  Arguments as q8_embedding_sum3 and q8_layernorm_absmax.  A token with an id outside
+ * its table counts as an all-zero row (its output row is beta) and sets err_flag[0] = 1.
+ */
+q8_status q8_embedding_sum3_layernorm(const int8_t* word, int64_t Vw, const int8_t* pos, int64_t Vp,
+                                      const int8_t* type, int64_t Vt, const float* scales, int64_t H,
+                                      const int32_t* wid, const int32_t* pid, const int32_t* tid, int64_t T,
+                                      const float* gamma, const float* beta, float eps,
+                                      float* y, float* amax_slots, int32_t* err_flag, void* stream);
 
 /* Library version string and a short text for a status code (host pointers, static storage). */
 const char* q8_version(void);

@@ -1,0 +1,291 @@
+// FP32 glue next to the quantized FC layers: Layer Normalization (Section 3 keeps it in FP32)
+// fused with what surrounds it on the dynamic-quantization path -- the residual addition or the
+// three-table int8 embedding lookup in front, and behind it the abs-max of its output, which is
+// the first half of the next FC layer's quantizer (Section 4.1).  One pass over HBM instead of
+// three or four: per element 4 B (+ 4 B residual, or 3 B of int8 codes) read and 4 B written.
+//
+// A wave owns a row.  The row lives in registers (up to 2048 columns); its sum and its sum of
+// squared deviations are accumulated in binary64 and reduced across the wave in a fixed order,
+// and the normalisation itself runs in binary64 with one final rounding, so the result is within
+// an ulp of the exact one and the same bytes come out on every run.  The kernel is bound by
+// memory: the binary64 arithmetic (about ten operations per element) hides under the loads.
+#include "q8_device.h"
+#include "q8_launch.h"
+
+namespace q8 {
+
+constexpr int kLnThreads = 256;            // four waves = four rows per workgroup per trip
+constexpr int kLnMaxVec = 8;               // float4 vectors per lane: rows up to 64 * 4 * 8 = 2048 columns
+constexpr int kLnSlots = 2048;             // abs-max slots (= Q8_AMAX_SLOTS): one per workgroup, the rest zero
+
+__device__ __forceinline__ double wave_sum_f64(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+struct EmbedSrc {
+    const unsigned *word, *pos, *typ;  // int8 tables viewed as packed dwords
+    int64_t Vw, Vp, Vt;
+    const float* scales;
+    const int32_t *wid, *pid, *tid;
+    int32_t* err_flag;
+};
+
+__device__ __forceinline__ float4 dequant4_ln(unsigned packed, float r)
+{
+    float4 o;
+    o.x = (float)(int)(int8_t)(packed & 0xff) * r;
+    o.y = (float)(int)(int8_t)((packed >> 8) & 0xff) * r;
+    o.z = (float)(int)(int8_t)((packed >> 16) & 0xff) * r;
+    o.w = (float)(int)(int8_t)(packed >> 24) * r;
+    return o;
+}
+
+// kSrc: 0 = x is a; 1 = x is a + r (one binary32 addition); 2 = x is the sum of three
+// dequantized embedding rows, (word + position) + type as in the plain lookup.
+// H % 4 == 0, H <= 2048, every pointer 16-byte aligned (tables 4-byte).
+template <int kSrc>
+__global__ __launch_bounds__(kLnThreads) void layernorm_rows_kernel(const float* a, const float* r, EmbedSrc es,
+                                                                     const float* __restrict__ gamma,
+                                                                     const float* __restrict__ beta, double eps,
+                                                                     int64_t M, int H, float* y,
+                                                                     unsigned* __restrict__ amax_slots)
+{
+    __shared__ unsigned wave_amax[kLnThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nvec = H >> 2;
+    float amax = 0.0f;
+    float r0 = 0.f, r1 = 0.f, r2 = 0.f;
+    if (kSrc == 2) {
+        r0 = __fdiv_rn(1.0f, es.scales[0]);
+        r1 = __fdiv_rn(1.0f, es.scales[1]);
+        r2 = __fdiv_rn(1.0f, es.scales[2]);
+    }
+    for (int64_t row = ((int64_t)blockIdx.x * (kLnThreads / 64)) + wave; row < M;
+         row += (int64_t)gridDim.x * (kLnThreads / 64)) {
+        float4 x[kLnMaxVec];
+        if (kSrc == 2) {
+            const int64_t ia = es.wid[row], ib = es.pid[row], ic = es.tid[row];
+            const bool ok = ia >= 0 && ia < es.Vw && ib >= 0 && ib < es.Vp && ic >= 0 && ic < es.Vt;
+            if (!ok && es.err_flag && lane == 0) es.err_flag[0] = 1;
+            const unsigned* wr = es.word + (ok ? ia : 0) * nvec;
+            const unsigned* pr = es.pos + (ok ? ib : 0) * nvec;
+            const unsigned* tr = es.typ + (ok ? ic : 0) * nvec;
+#pragma unroll
+            for (int j = 0; j < kLnMaxVec; ++j) {
+                const int v = j * 64 + lane;
+                x[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (v < nvec && ok) {
+                    const float4 p = dequant4_ln(wr[v], r0), q = dequant4_ln(pr[v], r1), t = dequant4_ln(tr[v], r2);
+                    x[j] = make_float4((p.x + q.x) + t.x, (p.y + q.y) + t.y, (p.z + q.z) + t.z, (p.w + q.w) + t.w);
+                }
+            }
+        } else {
+            const float4* av = reinterpret_cast<const float4*>(a) + row * nvec;
+            const float4* rv = reinterpret_cast<const float4*>(r) + row * nvec;
+#pragma unroll
+            for (int j = 0; j < kLnMaxVec; ++j) {
+                const int v = j * 64 + lane;
+                x[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (v < nvec) {
+                    x[j] = av[v];
+                    if (kSrc == 1) {
+                        const float4 q = rv[v];
+                        x[j] = make_float4(__fadd_rn(x[j].x, q.x), __fadd_rn(x[j].y, q.y), __fadd_rn(x[j].z, q.z),
+                                           __fadd_rn(x[j].w, q.w));
+                    }
+                }
+            }
+        }
+        double s = 0.0;
+#pragma unroll
+        for (int j = 0; j < kLnMaxVec; ++j)  // lanes past the row hold zeros
+            s += ((double)x[j].x + (double)x[j].y) + ((double)x[j].z + (double)x[j].w);
+        const double mean = wave_sum_f64(s) / (double)H;
+        double ss = 0.0;
+#pragma unroll
+        for (int j = 0; j < kLnMaxVec; ++j) {
+            if (j * 64 + lane < nvec) {
+                const double d0 = (double)x[j].x - mean, d1 = (double)x[j].y - mean;
+                const double d2 = (double)x[j].z - mean, d3 = (double)x[j].w - mean;
+                ss += (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
+            }
+        }
+        const double rstd = 1.0 / sqrt(wave_sum_f64(ss) / (double)H + eps);
+        float4* yv = reinterpret_cast<float4*>(y) + row * nvec;
+#pragma unroll
+        for (int j = 0; j < kLnMaxVec; ++j) {
+            const int v = j * 64 + lane;
+            if (v < nvec) {
+                const float4 g = reinterpret_cast<const float4*>(gamma)[v], b = reinterpret_cast<const float4*>(beta)[v];
+                float4 o;
+                o.x = (float)(((double)x[j].x - mean) * rstd * (double)g.x + (double)b.x);
+                o.y = (float)(((double)x[j].y - mean) * rstd * (double)g.y + (double)b.y);
+                o.z = (float)(((double)x[j].z - mean) * rstd * (double)g.z + (double)b.z);
+                o.w = (float)(((double)x[j].w - mean) * rstd * (double)g.w + (double)b.w);
+                yv[v] = o;
+                amax = __builtin_fmaxf(amax, __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(o.x), __builtin_fabsf(o.y)),
+                                                            __builtin_fmaxf(__builtin_fabsf(o.z), __builtin_fabsf(o.w))));
+            }
+        }
+    }
+    if (amax_slots) {
+        unsigned m = wave_max_u32(__float_as_uint(amax));  // non-negative floats order like their bit patterns
+        if (lane == 0) wave_amax[wave] = m;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+#pragma unroll
+            for (int w = 1; w < kLnThreads / 64; ++w) m = max(m, wave_amax[w]);
+            amax_slots[blockIdx.x] = m;
+        }
+        if (blockIdx.x == 0)  // slots no workgroup owns
+            for (int i = gridDim.x + threadIdx.x; i < kLnSlots; i += kLnThreads) amax_slots[i] = 0u;
+    }
+}
+
+// Any H and alignment: a wave per row, three passes over the row (the second and third come
+// from cache).  Same arithmetic; rows are read element by element.
+template <int kSrc>
+__global__ __launch_bounds__(kLnThreads) void layernorm_generic_kernel(const float* a, const float* r, EmbedSrc es,
+                                                                        const int8_t* word8, const int8_t* pos8,
+                                                                        const int8_t* typ8,
+                                                                        const float* __restrict__ gamma,
+                                                                        const float* __restrict__ beta, double eps,
+                                                                        int64_t M, int64_t H, float* y,
+                                                                        unsigned* __restrict__ amax_slots)
+{
+    __shared__ unsigned wave_amax[kLnThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float amax = 0.0f;
+    float r0 = 0.f, r1 = 0.f, r2 = 0.f;
+    if (kSrc == 2) {
+        r0 = __fdiv_rn(1.0f, es.scales[0]);
+        r1 = __fdiv_rn(1.0f, es.scales[1]);
+        r2 = __fdiv_rn(1.0f, es.scales[2]);
+    }
+    for (int64_t row = ((int64_t)blockIdx.x * (kLnThreads / 64)) + wave; row < M;
+         row += (int64_t)gridDim.x * (kLnThreads / 64)) {
+        int64_t ia = 0, ib = 0, ic = 0;
+        bool ok = true;
+        if (kSrc == 2) {
+            ia = es.wid[row], ib = es.pid[row], ic = es.tid[row];
+            ok = ia >= 0 && ia < es.Vw && ib >= 0 && ib < es.Vp && ic >= 0 && ic < es.Vt;
+            if (!ok && es.err_flag && lane == 0) es.err_flag[0] = 1;
+        }
+        auto value = [&](int64_t h) -> float {
+            if (kSrc == 2) {
+                if (!ok) return 0.0f;
+                const float p = (float)(int)word8[ia * H + h] * r0, q = (float)(int)pos8[ib * H + h] * r1;
+                const float t = (float)(int)typ8[ic * H + h] * r2;
+                return (p + q) + t;
+            }
+            const float v = a[row * H + h];
+            return kSrc == 1 ? __fadd_rn(v, r[row * H + h]) : v;
+        };
+        double s = 0.0;
+        for (int64_t h = lane; h < H; h += 64) s += (double)value(h);
+        const double mean = wave_sum_f64(s) / (double)H;
+        double ss = 0.0;
+        for (int64_t h = lane; h < H; h += 64) {
+            const double d = (double)value(h) - mean;
+            ss += d * d;
+        }
+        const double rstd = 1.0 / sqrt(wave_sum_f64(ss) / (double)H + eps);
+        for (int64_t h = lane; h < H; h += 64) {
+            const float o = (float)(((double)value(h) - mean) * rstd * (double)gamma[h] + (double)beta[h]);
+            y[row * H + h] = o;
+            amax = __builtin_fmaxf(amax, __builtin_fabsf(o));
+        }
+    }
+    if (amax_slots) {
+        unsigned m = wave_max_u32(__float_as_uint(amax));
+        if (lane == 0) wave_amax[wave] = m;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+#pragma unroll
+            for (int w = 1; w < kLnThreads / 64; ++w) m = max(m, wave_amax[w]);
+            amax_slots[blockIdx.x] = m;
+        }
+        if (blockIdx.x == 0)
+            for (int i = gridDim.x + threadIdx.x; i < kLnSlots; i += kLnThreads) amax_slots[i] = 0u;
+    }
+}
+
+__global__ void amax_slots_clear_kernel(unsigned* slots)
+{
+    for (int i = threadIdx.x; i < kLnSlots; i += kLnThreads) slots[i] = 0u;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+static int ln_grid(int64_t M)
+{
+    int64_t g = (M + kLnThreads / 64 - 1) / (kLnThreads / 64);
+    return (int)(g < 1 ? 1 : (g < kLnSlots ? g : kLnSlots));
+}
+
+int launch_layernorm(const float* a, const float* r, const float* gamma, const float* beta, float eps, int64_t M,
+                     int64_t H, float* y, float* amax_slots, hipStream_t st)
+{
+    unsigned* slots = reinterpret_cast<unsigned*>(amax_slots);
+    if (M == 0) {
+        if (slots) hipLaunchKernelGGL(amax_slots_clear_kernel, dim3(1), dim3(kLnThreads), 0, st, slots);
+        return hipGetLastError() == hipSuccess ? 0 : 1;
+    }
+    EmbedSrc es = {};
+    const bool fast = H % 4 == 0 && H <= 64 * 4 * kLnMaxVec && aligned16(a) && aligned16(y) && aligned16(gamma) &&
+                      aligned16(beta) && (!r || aligned16(r));
+    const dim3 grid(ln_grid(M)), block(kLnThreads);
+    if (fast) {
+        if (r)
+            hipLaunchKernelGGL(layernorm_rows_kernel<1>, grid, block, 0, st, a, r, es, gamma, beta, (double)eps, M,
+                               (int)H, y, slots);
+        else
+            hipLaunchKernelGGL(layernorm_rows_kernel<0>, grid, block, 0, st, a, r, es, gamma, beta, (double)eps, M,
+                               (int)H, y, slots);
+    } else {
+        if (r)
+            hipLaunchKernelGGL(layernorm_generic_kernel<1>, grid, block, 0, st, a, r, es, nullptr, nullptr, nullptr,
+                               gamma, beta, (double)eps, M, H, y, slots);
+        else
+            hipLaunchKernelGGL(layernorm_generic_kernel<0>, grid, block, 0, st, a, r, es, nullptr, nullptr, nullptr,
+                               gamma, beta, (double)eps, M, H, y, slots);
+    }
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+int launch_embedding_sum3_layernorm(const int8_t* word, int64_t Vw, const int8_t* pos, int64_t Vp, const int8_t* typ,
+                                    int64_t Vt, const float* scales, int64_t H, const int32_t* wid,
+                                    const int32_t* pid, const int32_t* tid, int64_t T, const float* gamma,
+                                    const float* beta, float eps, float* y, float* amax_slots, int32_t* err_flag,
+                                    hipStream_t st)
+{
+    unsigned* slots = reinterpret_cast<unsigned*>(amax_slots);
+    if (T == 0) {
+        if (slots) hipLaunchKernelGGL(amax_slots_clear_kernel, dim3(1), dim3(kLnThreads), 0, st, slots);
+        return hipGetLastError() == hipSuccess ? 0 : 1;
+    }
+    EmbedSrc es;
+    es.word = reinterpret_cast<const unsigned*>(word);
+    es.pos = reinterpret_cast<const unsigned*>(pos);
+    es.typ = reinterpret_cast<const unsigned*>(typ);
+    es.Vw = Vw, es.Vp = Vp, es.Vt = Vt;
+    es.scales = scales;
+    es.wid = wid, es.pid = pid, es.tid = tid;
+    es.err_flag = err_flag;
+    const auto a4 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3) == 0; };
+    const bool fast = H % 4 == 0 && H <= 64 * 4 * kLnMaxVec && a4(word) && a4(pos) && a4(typ) && aligned16(y) &&
+                      aligned16(gamma) && aligned16(beta);
+    const dim3 grid(ln_grid(T)), block(kLnThreads);
+    if (fast)
+        hipLaunchKernelGGL(layernorm_rows_kernel<2>, grid, block, 0, st, nullptr, nullptr, es, gamma, beta,
+                           (double)eps, T, (int)H, y, slots);
+    else
+        hipLaunchKernelGGL(layernorm_generic_kernel<2>, grid, block, 0, st, nullptr, nullptr, es, word, pos, typ, gamma,
+                           beta, (double)eps, T, H, y, slots);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+}  // namespace q8

@@ -1,0 +1,152 @@
+"""GPU parity of the fused LayerNorm entry points against the CPU oracle.  LayerNorm is FP32 glue
+(Section 3), computed on the GPU with binary64 statistics and one final rounding, so y must agree with
+the oracle's binary64 evaluation within 1e-6 relative (a couple of ulps); the abs-max slots are exact
+with respect to the y the GPU itself wrote, and the codes of the quantizer fed from them are bit-exact
+with the oracle's quantization of that y (stage-wise rule)."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from oracle import q8_oracle as O  # noqa: E402
+from paper_1910_06188_amd import synth  # noqa: E402
+
+RTOL, ATOL = 1e-6, 2e-7      # atol: outputs near zero, where the oracle's own last rounding is of this size
+
+
+@pytest.fixture(scope="module")
+def q8():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1910_06188_amd import q8 as mod
+    return mod
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def close(got, ref):
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+    tol = ATOL + RTOL * np.abs(ref.astype(np.float64))
+    assert not (err > tol).any(), f"worst err/tol {np.max(err / tol):.2f}"
+
+
+def params(g, H):
+    return (1 + 0.1 * g.standard_normal(H)).astype(np.float32), (0.1 * g.standard_normal(H)).astype(np.float32)
+
+
+@pytest.mark.parametrize("M,H", [(1, 4), (5, 768), (16, 768), (333, 1024), (4096, 768), (7, 2048), (9, 2052), (6, 770), (3, 1), (2, 4100)])
+@pytest.mark.parametrize("with_residual", [False, True])
+def test_layernorm_absmax(q8, M, H, with_residual):
+    g = synth.rng(400 + M + H)
+    a = synth.activations(g, M, H) * np.float32(2.5) + np.float32(0.3)
+    r = synth.activations(g, M, H) if with_residual else None
+    gamma, beta = params(g, H)
+    y = torch.full((M, H), 9.0, device="cuda")
+    slots = torch.full((q8.AMAX_SLOTS,), -1.0, device="cuda")
+    q8.q8_layernorm_absmax(dev(a), dev(gamma), dev(beta), y, eps=1e-12, residual=None if r is None else dev(r), amax_slots=slots)
+    ref = O.layernorm(a, gamma, beta, eps=1e-12, residual=r)
+    got = host(y)
+    close(got, ref)
+    s = host(slots)
+    assert s.min() >= 0 and s.max() == np.abs(got).max()
+    # the slots feed the quantizer of the next FC: scale and codes follow from the GPU's own y
+    q = torch.empty((M, H), dtype=torch.int8, device="cuda")
+    sc, am = torch.zeros(1, device="cuda"), torch.zeros(1, device="cuda")
+    q8.q8_quantize_amax(y, slots, sc, q, amax_out=am)
+    assert host(am)[0] == np.abs(got).max() and host(sc)[0] == O.scale(np.abs(got).max())
+    np.testing.assert_array_equal(host(q), O.quantize(got, host(sc)[0]))
+    # without slots, and in place
+    ad = dev(a)
+    q8.q8_layernorm_absmax(ad, dev(gamma), dev(beta), ad, eps=1e-12, residual=None if r is None else dev(r))
+    np.testing.assert_array_equal(host(ad), got)
+
+
+def test_layernorm_edge_rows_and_views(q8):
+    g = synth.rng(41)
+    H = 768
+    gamma, beta = params(g, H)
+    # constant rows (zero variance) give beta; huge offsets do not lose the deviations
+    a = np.full((4, H), 3.25, dtype=np.float32)
+    a[2] = synth.activations(g, 1, H)[0] + np.float32(1000.0)
+    a[3] = synth.activations(g, 1, H)[0] * np.float32(1e-3)
+    y = torch.empty((4, H), device="cuda")
+    q8.q8_layernorm_absmax(dev(a), dev(gamma), dev(beta), y, eps=1e-12)
+    got = host(y)
+    np.testing.assert_array_equal(got[0], beta)
+    close(got, O.layernorm(a, gamma, beta, eps=1e-12))
+    # misaligned views take the generic kernel: same values as the aligned run
+    base = torch.zeros(4 * H + 8, device="cuda")
+    view = base[1:1 + 4 * H].view(4, H)
+    view.copy_(dev(a))
+    out = torch.zeros(4 * H + 8, device="cuda")
+    q8.q8_layernorm_absmax(view, dev(gamma), dev(beta), out[3:3 + 4 * H].view(4, H), eps=1e-12)
+    close(host(out)[3:3 + 4 * H].reshape(4, H), O.layernorm(a, gamma, beta, eps=1e-12))
+    assert host(out)[:3].tolist() == [0, 0, 0] and not host(out)[3 + 4 * H:].any()
+    # empty batch: every slot cleared
+    slots = torch.full((q8.AMAX_SLOTS,), 5.0, device="cuda")
+    q8.q8_layernorm_absmax(torch.empty((0, H), device="cuda"), dev(gamma), dev(beta), torch.empty((0, H), device="cuda"), amax_slots=slots)
+    assert not host(slots).any()
+
+
+@pytest.mark.parametrize("T,H,V", [(64, 768, 1000), (777, 1024, 30522), (50, 772, 300), (33, 100, 50)])
+def test_embedding_sum3_layernorm(q8, T, H, V):
+    g = synth.rng(500 + T)
+    tabs = synth.embedding_tables(seed=7, hidden=H, vocab=V)
+    q, s = {}, {}
+    for k in ("word", "position", "token_type"):
+        s[k] = O.scale(O.absmax(tabs[k]))
+        q[k] = O.quantize(tabs[k], s[k])
+    wid = g.integers(0, V, T).astype(np.int32)
+    pid = g.integers(0, tabs["position"].shape[0], T).astype(np.int32)
+    tid = g.integers(0, tabs["token_type"].shape[0], T).astype(np.int32)
+    wid[0], wid[-1] = 0, V - 1
+    gamma, beta = params(g, H)
+    scales = np.array([s["word"], s["position"], s["token_type"]], dtype=np.float32)
+    y = torch.empty((T, H), device="cuda")
+    slots = torch.zeros(q8.AMAX_SLOTS, device="cuda")
+    err = torch.zeros(1, dtype=torch.int32, device="cuda")
+    args = (dev(q["word"]), dev(q["position"]), dev(q["token_type"]), dev(scales))
+    q8.q8_embedding_sum3_layernorm(*args, dev(wid), dev(pid), dev(tid), dev(gamma), dev(beta), y, eps=1e-12, amax_slots=slots, err_flag=err)
+    assert int(err.item()) == 0
+    # the summed rows the GPU's plain lookup writes are the LayerNorm's input (stage-wise rule)
+    summed = torch.empty((T, H), device="cuda")
+    q8.q8_embedding_sum3(*args, dev(wid), dev(pid), dev(tid), summed)
+    ref = O.layernorm(host(summed), gamma, beta, eps=1e-12)
+    got = host(y)
+    close(got, ref)
+    assert host(slots).max() == np.abs(got).max()
+    # and the lookup itself against the oracle, so the chain is pinned end to end
+    emb = O.embedding_sum3(q["word"], s["word"], q["position"], s["position"], q["token_type"], s["token_type"], wid, pid, tid)
+    mag = (np.abs(q["word"][wid].astype(np.float64)) / float(s["word"]) + np.abs(q["position"][pid].astype(np.float64)) / float(s["position"])
+           + np.abs(q["token_type"][tid].astype(np.float64)) / float(s["token_type"]))     # three fp32 terms: tolerance scaled by their sizes
+    assert np.all(np.abs(host(summed).astype(np.float64) - emb) <= 1e-6 * mag + 1e-12)
+    # a bad id: zero row -> beta, flag raised, nothing else disturbed
+    wid_bad = wid.copy()
+    wid_bad[T // 2] = V
+    q8.q8_embedding_sum3_layernorm(*args, dev(wid_bad), dev(pid), dev(tid), dev(gamma), dev(beta), y, eps=1e-12, err_flag=err)
+    assert int(err.item()) == 1
+    got2 = host(y)
+    np.testing.assert_array_equal(got2[T // 2], beta)
+    np.testing.assert_array_equal(np.delete(got2, T // 2, 0), np.delete(got, T // 2, 0))
+
+
+def test_layernorm_argument_checks(q8):
+    lib = q8.raw()
+    x = torch.zeros(16, device="cuda")
+    p = x.data_ptr()
+    assert lib.q8_layernorm_absmax(p, None, p, p, 1e-12, -1, 4, p, None, None) == 2
+    assert lib.q8_layernorm_absmax(p, None, p, p, 1e-12, 4, 0, p, None, None) == 2
+    assert lib.q8_layernorm_absmax(p, None, p, p, -1.0, 4, 4, p, None, None) == 2
+    assert lib.q8_layernorm_absmax(None, None, p, p, 1e-12, 4, 4, p, None, None) == 1
+    assert lib.q8_layernorm_absmax(p, None, None, p, 1e-12, 4, 4, p, None, None) == 1
+    assert lib.q8_layernorm_absmax(p + 2, None, p, p, 1e-12, 1, 4, p, None, None) == 3
+    assert lib.q8_embedding_sum3_layernorm(p, 4, p, 4, p, 4, p, 4, None, p, p, 2, p, p, 1e-12, p, None, None, None) == 1
+    assert lib.q8_embedding_sum3_layernorm(p, 4, p, 4, p, 4, p, 0, p, p, p, 2, p, p, 1e-12, p, None, None, None) == 2
+    torch.cuda.synchronize()
