@@ -322,7 +322,9 @@ int launch_absmax(const float* x, int64_t n, float* amax_out, float* scale_out, 
     unsigned* bits = reinterpret_cast<unsigned*>(amax_out);
     const int head = head_of(x, n);
     hipLaunchKernelGGL(absmax_init_kernel, dim3(1), dim3(1), 0, st, bits);
-    hipLaunchKernelGGL(absmax_atomic_kernel, dim3(am_grid((n - head) >> 2)), dim3(kEwThreads), 0, st, x, n, head, bits);
+    // two workgroups per compute unit at most: every workgroup ends in a read or read-modify-write of one address
+    const int g = am_grid((n - head) >> 2);
+    hipLaunchKernelGGL(absmax_atomic_kernel, dim3(g < 512 ? g : 512), dim3(kEwThreads), 0, st, x, n, head, bits);
     if (scale_out) hipLaunchKernelGGL(scale_from_amax_kernel, dim3(1), dim3(1), 0, st, amax_out, scale_out);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
