@@ -349,6 +349,31 @@ def main():
                                    "note": "dynamic scales; adds embedding+LayerNorm and the layer's two residual+LayerNorm "
                                            "passes to the step and drops the abs-max passes of QKV and FFN1 (their abs-max "
                                            "comes out of the LayerNorm kernels)"}
+    # the memory-bound kernels on their own: achieved bytes/s against the 8 TB/s of the HBM (algorithmic bytes)
+    def hbm_rate(fn, nbytes, reps=20):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) * 1e3 / reps
+        return {"us_per_call": round(us, 1), "GBps": round(nbytes / us / 1e3, 1), "frac_of_8TBps": round(nbytes / us / 1e3 / 8000.0, 3)}
+    big, nbig = layer.g, layer.g.numel()
+    xq_big = layer.xq[:nbig]
+    out["hbm_kernels"] = {
+        "q8_absmax fp32[12288,4096] (4 B/elt; 3 launches)": hbm_rate(lambda: q8.q8_absmax(big, layer.gscal[0:1], layer.gscal[1:2]), 4.0 * nbig),
+        "q8_quantize fp32[12288,4096] (5 B/elt)": hbm_rate(lambda: q8.q8_quantize(big, layer.gscal[1:2], xq_big), 5.0 * nbig),
+        "q8_embedding_sum3 12288 tokens x 1024 (3 int8 rows in, fp32 row out)": hbm_rate(
+            lambda: q8.q8_embedding_sum3(layer.tables[0], layer.tables[1], layer.tables[2], layer.table_scales, layer.ids[0],
+                                         layer.ids[1], layer.ids[2], layer.emb, err_flag=layer.err), layer.M * (3.0 * layer.H + 12 + 4.0 * layer.H)),
+        "q8_layernorm_absmax fp32[12288,1024] + residual (12 B/elt)": hbm_rate(
+            lambda: q8.q8_layernorm_absmax(layer.x, layer.ln_g, layer.ln_b, layer.h1f, residual=layer.attn_out, amax_slots=layer.slots_h),
+            12.0 * layer.M * layer.H),
+    }
     # training-side quantizer (Section 2.2 / Eq. 4): abs-max, moving-average step and fake quantization
     # of the FFN2-input-sized activation; bound by HBM (4 B read for the abs-max, 4 B + 4 B for the rest)
     xs = layer.g
