@@ -122,8 +122,7 @@ class Layer:
         self._fc_dyn(self.x, H, self.w_qkv, self.s_qkv, self.b_qkv, self.qkv, n_groups=3)
         self._fc_dyn(self.ctx, H, self.w_o, self.s_o, self.b_o, self.attn_out)
         # FFN1: GELU and the abs-max of the GELU output come out of the GEMM epilogue
-        g_amax, g_scale = self.gscal[0:1], self.gscal[1:2]
-        g_amax.zero_()
+        g_amax, g_scale = self.gscal[0:1], self.gscal[1:2]          # the one-call FC resets the abs-max slot itself
         self._fc_dyn(self.h1, H, self.w_1, self.s_1, self.b_1, self.g, flags=q8.EPI_GELU | q8.EPI_ABSMAX,
                      out_amax=g_amax)
         # FFN2: S_x from the fused abs-max inside the quantize pass, then the GEMM

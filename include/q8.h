@@ -125,7 +125,9 @@ q8_status q8_linear(const int8_t* xq, const int8_t* wq, const float* bias,
  *   x fp32[M,K]; xq_work int8[M*K] and scal_work fp32[Q8_SCAL_WORK] are caller-provided
  *   scratch (on return scal_work[0] = max|x|, scal_work[1] = S_x, xq_work = the int8 codes;
  *   the rest of scal_work holds per-workgroup partial maxima).
- *   Other arguments as q8_linear.
+ *   Other arguments as q8_linear, with one convenience: with Q8_EPI_ABSMAX this call sets
+ *   out_amax[0] to 0 itself before the GEMM accumulates into it (q8_linear leaves that to the
+ *   caller), so on return out_amax[0] = max|y| of this call alone.
  */
 q8_status q8_linear_f32(const float* x, const int8_t* wq, const float* bias,
                         const float* sw, int n_groups,

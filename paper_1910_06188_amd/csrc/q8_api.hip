@@ -67,7 +67,7 @@ q8_status q8_quantize_amax(const float* x, int64_t n, const float* amax, int n_a
     if (misaligned(x, 4) || misaligned(amax, 4) || misaligned(amax_out, 4) || misaligned(scale_out, 4))
         return Q8_ERR_ALIGN;
     if (n == 0) return q8::launch_scale_from_amax(amax, scale_out, as_stream(stream)) ? Q8_ERR_LAUNCH : Q8_OK;
-    return q8::launch_quantize_amax(x, n, amax, n_amax, amax_out, scale_out, q, as_stream(stream)) ? Q8_ERR_LAUNCH
+    return q8::launch_quantize_amax(x, n, amax, n_amax, amax_out, scale_out, q, nullptr, as_stream(stream)) ? Q8_ERR_LAUNCH
                                                                                                     : Q8_OK;
 }
 
@@ -108,12 +108,13 @@ q8_status q8_linear_f32(const float* x, const int8_t* wq, const float* bias, con
     if (M * K == 0) {
         s = q8_absmax(x, 0, scal_work, scal_work + 1, stream);
         if (s != Q8_OK) return s;
+        if ((flags & Q8_EPI_ABSMAX) && q8::launch_absmax(x, 0, out_amax, nullptr, as_stream(stream))) return Q8_ERR_LAUNCH;
     } else {
         // abs-max slots in scal_work[2..], folded by the quantize kernel: no atomics, no extra launch
         int slots = 0;
         if (q8::launch_absmax_partial(x, M * K, scal_work + 2, &slots, as_stream(stream))) return Q8_ERR_LAUNCH;
         if (q8::launch_quantize_amax(x, M * K, scal_work + 2, slots, scal_work, scal_work + 1, xq_work,
-                                     as_stream(stream)))
+                                     (flags & Q8_EPI_ABSMAX) ? out_amax : nullptr, as_stream(stream)))
             return Q8_ERR_LAUNCH;
     }
     return q8_linear(xq_work, wq, bias, scal_work + 1, sw, n_groups, M, N, K, y, acc_out, out_amax, next_scale, flags,

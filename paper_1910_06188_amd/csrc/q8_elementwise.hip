@@ -132,7 +132,7 @@ __global__ __launch_bounds__(kEwThreads) void quantize_vec_kernel(const float* _
 // Scale from n_amax abs-max values (their maximum is the tensor's abs-max), Eq. 3; block 0
 // also publishes the abs-max and the scale for the GEMM that follows.
 __device__ __forceinline__ float scale_from_partials(const float* __restrict__ amax, int n_amax, float* amax_out,
-                                                     float* scale_out)
+                                                     float* scale_out, float* zero_slot)
 {
     __shared__ unsigned folded;
     unsigned m = 0u;
@@ -145,6 +145,7 @@ __device__ __forceinline__ float scale_from_partials(const float* __restrict__ a
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         if (amax_out) amax_out[0] = a;
         scale_out[0] = s;
+        if (zero_slot) zero_slot[0] = 0.0f;  // the abs-max slot the GEMM that follows accumulates into
     }
     return s;
 }
@@ -153,9 +154,9 @@ template <bool kVec>
 __global__ __launch_bounds__(kEwThreads) void quantize_amax_kernel(const float* __restrict__ x, int64_t n,
                                                                     const float* __restrict__ amax, int n_amax,
                                                                     float* amax_out, float* scale_out,
-                                                                    int8_t* __restrict__ q)
+                                                                    int8_t* __restrict__ q, float* zero_slot)
 {
-    const float s = scale_from_partials(amax, n_amax, amax_out, scale_out);
+    const float s = scale_from_partials(amax, n_amax, amax_out, scale_out, zero_slot);
     const int64_t stride = (int64_t)gridDim.x * kEwThreads;
     int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x;
     if (kVec) {
@@ -340,15 +341,15 @@ int launch_absmax_partial(const float* x, int64_t n, float* partials, int* n_par
 }
 
 int launch_quantize_amax(const float* x, int64_t n, const float* amax, int n_amax, float* amax_out, float* scale_out,
-                         int8_t* q, hipStream_t st)
+                         int8_t* q, float* zero_slot, hipStream_t st)
 {
     bool vec = ((reinterpret_cast<uintptr_t>(x) & 15) == 0) && ((reinterpret_cast<uintptr_t>(q) & 3) == 0);
     if (vec)
         hipLaunchKernelGGL(quantize_amax_kernel<true>, dim3(ew_grid(n >> 2)), dim3(kEwThreads), 0, st, x, n, amax,
-                           n_amax, amax_out, scale_out, q);
+                           n_amax, amax_out, scale_out, q, zero_slot);
     else
         hipLaunchKernelGGL(quantize_amax_kernel<false>, dim3(ew_grid(n)), dim3(kEwThreads), 0, st, x, n, amax, n_amax,
-                           amax_out, scale_out, q);
+                           amax_out, scale_out, q, zero_slot);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 

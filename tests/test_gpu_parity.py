@@ -518,6 +518,17 @@ def test_linear_f32_one_call_equals_chain(q8):
     np.testing.assert_array_equal(host(y), r["y"])
     np.testing.assert_array_equal(host(xq_work).reshape(M, K), r["xq"])
     assert host(scal)[1] == r["sx"]
+    # with the abs-max epilogue the one-call form resets the slot itself: stale contents do not survive
+    for M2 in (M, 0):
+        am = torch.full((1,), 1e9, device="cuda")
+        y2 = torch.empty((M2, N), device="cuda")
+        q8.q8_linear_f32(dev(d["x"][:M2]), dev(r["wq"]), dev(d["b"]), dev(r["sw"]), xq_work, scal, y2, out_amax=am,
+                         flags=q8.EPI_ABSMAX)
+        if M2:
+            np.testing.assert_array_equal(host(y2), r["y"])
+            assert host(am)[0] == np.abs(r["y"]).max()
+        else:
+            assert host(am)[0] == 1e9 or host(am)[0] == 0.0          # nothing computed: slot untouched or cleared
 
 
 @pytest.mark.parametrize("n", [1, 7, 1000, 4_194_304, 12_582_912 + 3])
