@@ -354,14 +354,17 @@ __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM*
     // per-lane column offset in a VGPR and the row offset in an SGPR: about six instructions
     // per element.  With one wave per SIMD the epilogue is bound by instruction issue, and
     // the bounds-checked path below costs twice as many.
-    const bool interior = (m0 + BM <= M) && (n0 + BN <= N) && ((int64_t)M * N * 4 < ((int64_t)1 << 31));
+    // The descriptors start at the tile's first row, so byte offsets stay below BM * N * 4 whatever
+    // the size of y (N * BM * 4 < 2^31 is all that is asked of the shape).
+    const bool interior = (m0 + BM <= M) && (n0 + BN <= N) && ((int64_t)N * BM * 4 < ((int64_t)1 << 31));
     if (interior) {
         const int esize = do_req ? 1 : 4;
-        const __amdgpu_buffer_rsrc_t ry =
-            __builtin_amdgcn_make_buffer_rsrc(ep.y, 0, (int)((unsigned)M * (unsigned)N * (unsigned)esize), 0x00020000);
+        const int64_t tile_row0 = (int64_t)m0 * N;
+        const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(
+            reinterpret_cast<char*>(ep.y) + tile_row0 * esize, 0, BM * N * esize, 0x00020000);
         const __amdgpu_buffer_rsrc_t racc = __builtin_amdgcn_make_buffer_rsrc(
-            ep.acc_out, 0, do_dump ? (int)((unsigned)M * (unsigned)N * 4u) : 0, 0x00020000);
-        const int row0 = m0 + wm * TM + 4 * hi;  // first row this lane stores
+            do_dump ? ep.acc_out + tile_row0 : ep.acc_out, 0, do_dump ? BM * N * 4 : 0, 0x00020000);
+        const int row0 = wm * TM + 4 * hi;  // first row this lane stores, counted from the tile's first row
         // An fp32 y larger than a quarter of the 256 MB Infinity Cache is stored non-temporally:
         // it could not stay cached until its consumer runs anyway, and kept out it neither evicts
         // the next kernels' inputs nor leaves dirty lines to drain under them (whole BERT-Large

@@ -119,3 +119,38 @@ def test_fullsize_embedding_bert_base_tables(q8):
     o8 = torch.empty((64 * 128, 768), dtype=torch.int8, device="cuda")
     q8.q8_embedding(dev(qs["word"][0]), scales[0:1], dev(ids["word"]), o8)
     np.testing.assert_array_equal(o8.cpu().numpy(), qs["word"][0][ids["word"]])
+
+
+def test_output_beyond_2_gib(q8):
+    """y and the accumulator dump larger than 2^31 bytes each (140000 x 4096 fp32 = 2.29 GB): the MFMA
+    kernel addresses its stores from each tile's first row, so the size of y does not matter.  Rows on both
+    sides of the 2^31-byte boundary, the first, the last full tile and the ragged last rows are compared
+    with the oracle; every tile shape."""
+    M, N, K = 140000, 4096, 128
+    g = synth.rng(77)
+    xq = synth.random_int8(g, (M, K))
+    wq = synth.random_int8(g, (N, K))
+    b = synth.bias(g, N)
+    sx, sw = np.float32(31.5), np.float32(1270.0)
+    rows = np.array([0, 1, 191, 192, 131071, 131072, 131073, 139775, 139776, 139999])     # 2^31 / (4096*4) = 131072
+    bq = O.quantize_bias(b, N, sx, np.array([sw], np.float32))
+    acc_ref = O.gemm_i8(xq[rows], wq, bq)
+    y_ref = O.dequant(acc_ref, sx, np.array([sw], np.float32))
+    xd, wd, bd = dev(xq), dev(wq), dev(b)
+    sxd, swd = torch.tensor([float(sx)], device="cuda"), torch.tensor([float(sw)], device="cuda")
+    y = torch.empty((M, N), device="cuda")
+    acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    ridx = torch.from_numpy(rows).cuda()
+    for variant in (0, 2, 3, 5, 6):
+        q8.set_gemm_variant(variant)
+        try:
+            y.zero_()
+            q8.q8_linear(xd, wd, bd, sxd, swd, y)                      # specialised kernel
+            got = y[ridx].cpu().numpy()
+            assert np.all(np.abs(got.astype(np.float64) - y_ref) <= 1e-6 * np.abs(y_ref.astype(np.float64))), variant
+            y.zero_()
+            q8.q8_linear(xd, wd, bd, sxd, swd, y, acc_out=acc)          # run-time-flag kernel with the dump
+            np.testing.assert_array_equal(acc[ridx].cpu().numpy(), acc_ref, err_msg=f"variant {variant}")
+            np.testing.assert_array_equal(y[ridx].cpu().numpy(), got)
+        finally:
+            q8.set_gemm_variant(0)
