@@ -34,7 +34,7 @@ extern "C" {
 typedef enum {
     Q8_OK = 0,
     Q8_ERR_NULL = 1,   /* a required pointer is NULL */
-    Q8_ERR_SHAPE = 2,  /* negative size, K above Q8_MAX_K, n_groups not dividing N, tensor above 2^32-1 bytes */
+    Q8_ERR_SHAPE = 2,  /* negative size, K above Q8_MAX_K, n_groups not dividing N, more than 2^39 output elements */
     Q8_ERR_ALIGN = 3,  /* a pointer breaks the alignment its type needs (4 bytes for float/int32) */
     Q8_ERR_FLAGS = 4,  /* unknown epilogue bit, or a flag without the pointer it needs */
     Q8_ERR_LAUNCH = 5  /* the HIP runtime refused a launch */

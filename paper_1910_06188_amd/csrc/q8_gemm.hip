@@ -61,8 +61,8 @@ bool gemm_mfma_eligible(const int8_t* xq, const int8_t* wq, int64_t M, int64_t N
 {
     if (K < kBK || K % kBK != 0) return false;
     if ((reinterpret_cast<uintptr_t>(xq) & 15) || (reinterpret_cast<uintptr_t>(wq) & 15)) return false;
-    const int64_t lim = (int64_t)1 << 31;  // buffer offsets and sizes stay in 31 bits
-    if (M * K >= lim || N * K >= lim || M * N >= ((int64_t)1 << 40)) return false;
+    const int64_t lim = (int64_t)1 << 31;  // M, N and the tile count are ints in the kernel; buffers are addressed per tile
+    if (M >= lim || N >= lim || ((M + 127) / 128) * ((N + 127) / 128) >= lim) return false;
     return M > 0 && N > 0;
 }
 

@@ -184,7 +184,12 @@ __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM*
     const int m0 = (pid / tiles_n) * BM;
     const int n0 = (pid % tiles_n) * BN;
 
-    const unsigned bytes_a = (unsigned)M * (unsigned)K, bytes_b = (unsigned)N * (unsigned)K;
+    // Operand descriptors start at the tile's first row, so the 32-bit offsets only span one tile
+    // (at most 256 rows x K bytes) however large the matrices are.
+    const int rows_a = min(BM, M - m0), rows_b = min(BN, N - n0);
+    const unsigned bytes_a = (unsigned)rows_a * (unsigned)K, bytes_b = (unsigned)rows_b * (unsigned)K;
+    const int8_t* Xt = X + (int64_t)m0 * K;
+    const int8_t* Wt = W + (int64_t)n0 * K;
 
     // Per-lane global byte offsets of this lane's chunk in each wave load (k = 0).  One
     // wave load covers 8 rows x 128 B; lane l fills row l/8, slot l%8 of the LDS side.
@@ -194,13 +199,13 @@ __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM*
     for (int i = 0; i < A_LOADS; ++i) {
         int r = (wave * A_LOADS + i) * 8 + (lane >> 3);
         int c = (lane & 7) ^ swizzle_of_row(r);
-        a_off[i] = (unsigned)min(m0 + r, M - 1) * (unsigned)K + (unsigned)(c * 16);
+        a_off[i] = (unsigned)min(r, rows_a - 1) * (unsigned)K + (unsigned)(c * 16);
     }
 #pragma unroll
     for (int i = 0; i < B_LOADS; ++i) {
         int r = (wave * B_LOADS + i) * 8 + (lane >> 3);
         int c = (lane & 7) ^ swizzle_of_row(r);
-        b_off[i] = (unsigned)min(n0 + r, N - 1) * (unsigned)K + (unsigned)(c * 16);
+        b_off[i] = (unsigned)min(r, rows_b - 1) * (unsigned)K + (unsigned)(c * 16);
     }
 
     const int KT = K / kBK;
@@ -211,12 +216,12 @@ __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM*
     };
     auto src_a = [&](int kt, int slot) {
         const bool live = kt < KT;  // past the end of K: empty descriptor, nothing is fetched
-        return Src{make_rsrc(X, live ? bytes_a : 0u), live ? (unsigned)(kt * kBK) : 0u,
+        return Src{make_rsrc(Xt, live ? bytes_a : 0u), live ? (unsigned)(kt * kBK) : 0u,
                    lds_base + (unsigned)(slot * A_BYTES + wave * A_LOADS * 1024)};
     };
     auto src_b = [&](int kt, int slot) {
         const bool live = kt < KT;
-        return Src{make_rsrc(W, live ? bytes_b : 0u), live ? (unsigned)(kt * kBK) : 0u,
+        return Src{make_rsrc(Wt, live ? bytes_b : 0u), live ? (unsigned)(kt * kBK) : 0u,
                    lds_base + (unsigned)(B_RING + slot * B_BYTES + wave * B_LOADS * 1024)};
     };
     auto load_all_a = [&](const Src& q) {

@@ -38,7 +38,7 @@ int launch_ema_update(const float* amax, int n_amax, float decay, float* state, 
 int launch_ste_backward(const float* g, int64_t n, float* gx, hipStream_t st);
 
 // True when the MFMA kernel can take the problem (K % 128 == 0, K >= 128, 16-byte
-// aligned operands, each operand below 2^32 bytes).
+// aligned operands; operands and output may be of any size, they are addressed per tile).
 bool gemm_mfma_eligible(const int8_t* xq, const int8_t* wq, int64_t M, int64_t N, int64_t K);
 int launch_gemm_mfma(const int8_t* xq, const int8_t* wq, int64_t M, int64_t N, int64_t K, const Epilogue& ep,
                      hipStream_t st);

@@ -154,3 +154,32 @@ def test_output_beyond_2_gib(q8):
             np.testing.assert_array_equal(y[ridx].cpu().numpy(), got)
         finally:
             q8.set_gemm_variant(0)
+
+
+def test_operand_beyond_2_gib(q8):
+    """An activation tensor larger than 2^31 bytes (524388 x 4096 int8 codes): the MFMA kernel addresses its
+    operand loads from each tile's first row as well.  Rows around the 2^31-byte boundary and the ragged
+    end against the oracle."""
+    M, N, K = 524388, 256, 4096
+    g = synth.rng(78)
+    xq = synth.random_int8(g, (M, K))
+    wq = synth.random_int8(g, (N, K))
+    b = synth.bias(g, N)
+    sx, sw = np.float32(31.5), np.float32(1270.0)
+    rows = np.array([0, 255, 256, 524287, 524288, 524289, 524387])          # 2^31 / 4096 = 524288
+    bq = O.quantize_bias(b, N, sx, np.array([sw], np.float32))
+    acc_ref = O.gemm_i8(xq[rows], wq, bq)
+    y_ref = O.dequant(acc_ref, sx, np.array([sw], np.float32))
+    xd, wd, bd = dev(xq), dev(wq), dev(b)
+    sxd, swd = torch.tensor([float(sx)], device="cuda"), torch.tensor([float(sw)], device="cuda")
+    y = torch.empty((M, N), device="cuda")
+    ridx = torch.from_numpy(rows).cuda()
+    for variant in (0, 3, 5):
+        q8.set_gemm_variant(variant)
+        try:
+            y.zero_()
+            q8.q8_linear(xd, wd, bd, sxd, swd, y)
+            got = y[ridx].cpu().numpy()
+            assert np.all(np.abs(got.astype(np.float64) - y_ref) <= 1e-6 * np.abs(y_ref.astype(np.float64))), variant
+        finally:
+            q8.set_gemm_variant(0)
