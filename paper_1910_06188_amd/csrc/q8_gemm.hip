@@ -6,7 +6,7 @@
 // Both operands are K-contiguous ("NT" GEMM), so a 16-byte vector of either one is
 // 16 consecutive k of one row -- exactly one lane's share of an i8 MFMA operand.
 //
-// MFMA kernel: a workgroup owns a BM x BN tile of y and walks K in stages of 64 bytes.
+// MFMA kernel: a workgroup owns a BM x BN tile of y and walks K in stages of 128 bytes.
 // Operand tiles go HBM/L2 -> LDS directly (buffer_load ... lds, 16 B per lane) into a
 // ring of stage buffers; waves read 16-byte fragments back (ds_read_b128) and issue
 // v_mfma_i32_32x32x32_i8.  LDS rows are swizzled so fragment reads are free of bank

@@ -9,7 +9,6 @@
 
 namespace q8 {
 
-
 constexpr int kBK = 128;  // bytes (= int8 elements) of K per LDS row and per pipeline stage: one full
                           // 128-byte cache line of every operand row, so no line is fetched twice
 constexpr int kKS = kBK / 32;  // 32-byte MFMA k-steps per stage
@@ -22,21 +21,6 @@ __device__ __forceinline__ int swizzle_of_row(int r) { return (r ^ (r >> 3)) & 7
 // s_waitcnt immediates for gfx9: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8.
 __host__ __device__ constexpr int waitcnt_vm(int vm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4) | (15 << 8); }
 __host__ __device__ constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4); }
-
-// Scheduling recipe for one k-step: the LDS reads and global loads are spread evenly
-// behind the MFMAs, so each memory operation issues in the shadow of a running MFMA.
-template <int MFMAS, int DSREADS, int VMEMS, int I = 0>
-__device__ __forceinline__ void interleave()
-{
-    if constexpr (I < MFMAS) {
-        constexpr int ds = (DSREADS * (I + 1)) / MFMAS - (DSREADS * I) / MFMAS;
-        constexpr int vm = (VMEMS * (I + 1)) / MFMAS - (VMEMS * I) / MFMAS;
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);               // one MFMA
-        if constexpr (ds > 0) __builtin_amdgcn_sched_group_barrier(0x100, ds, 0);  // LDS reads
-        if constexpr (vm > 0) __builtin_amdgcn_sched_group_barrier(0x020, vm, 0);  // global loads
-        interleave<MFMAS, DSREADS, VMEMS, I + 1>();
-    }
-}
 
 // Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous run of
 // tile ids so that the tiles sharing operand rows meet in the same L2.
@@ -103,6 +87,14 @@ __device__ __forceinline__ void static_for(F&& f)
     }
 }
 
+// Waves per SIMD the kernel is compiled for: a tile whose rings take at most half of the LDS is
+// meant to run as two workgroups per compute unit (one's epilogue under the other's main loop),
+// which only happens if each wave also stays within half of the register file.
+constexpr int mfma_waves_per_simd(int BM, int BN, int SB, int NW)
+{
+    return ((2 * BM + SB * BN) * kBK <= 80 * 1024 ? 2 : 1) * (NW / 4);
+}
+
 // Software-pipelined MFMA kernel.
 //
 // K is walked in stages of kBK = 128 bytes, four 32-byte k-steps each.  The x tile (A) and
@@ -132,14 +124,6 @@ __device__ __forceinline__ void static_for(F&& f)
 // Q8_EPI_ABSMAX (2) and Q8_EPI_REQUANT (4) with no accumulator dump; -1 = decide at run time
 // (any flags, optional dump).  With one wave per SIMD a per-element run-time branch costs
 // more than the arithmetic it guards, so the combinations that matter get their own kernel.
-// Waves per SIMD the kernel is compiled for: a tile whose rings take at most half of the LDS is
-// meant to run as two workgroups per compute unit (one's epilogue under the other's main loop),
-// which only happens if each wave also stays within half of the register file.
-constexpr int mfma_waves_per_simd(int BM, int BN, int SB, int NW)
-{
-    return ((2 * BM + SB * BN) * kBK <= 80 * 1024 ? 2 : 1) * (NW / 4);
-}
-
 template <int BM, int BN, int WGM, int WGN, int SB, int kEpi>
 __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM* WGN)) void gemm_mfma_kernel(const int8_t* __restrict__ X,
                                                                    const int8_t* __restrict__ W, int M, int N, int K,
