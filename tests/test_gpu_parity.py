@@ -328,6 +328,26 @@ def test_linear_random_int8_all_variants_asymmetric(q8):
         np.testing.assert_array_equal(host(acc), ref, err_msg=f"variant {variant}")
 
 
+def test_linear_random_shapes_every_variant(q8):
+    """Seeded random shapes (ragged in every dimension, K on and off the MFMA grid) through every tile
+    variant, with and without bias, one or three weight-scale groups: the whole dynamic chain against the
+    oracle, plus the dedicated fp32 kernel against the run-time-flag one."""
+    g = synth.rng(2024)
+    for case in range(28):
+        M = int(g.integers(1, 700))
+        K = int(g.choice([128, 256, 384, 512, 640])) if case % 4 else int(g.integers(1, 300))
+        n_groups = 3 if case % 3 == 0 else 1
+        N = int(g.integers(1, 260)) * n_groups
+        variant = case % 7
+        d = synth.fc_layer(3000 + case, M, K, N)
+        Ws = [d["W"][i * (N // n_groups):(i + 1) * (N // n_groups)] * np.float32(1 + 0.5 * i) for i in range(n_groups)]
+        b = d["b"] if case % 5 else None
+        r = run_linear(q8, d["x"], None, b, n_groups=n_groups, variant=variant, Ws=Ws)
+        ref = check_linear(r, d["x"], b)
+        assert_rel(r["y"], ref["y"])
+        np.testing.assert_array_equal(r["y_plain"], r["y"], err_msg=f"case {case}: M={M} K={K} N={N} variant={variant}")
+
+
 def test_linear_bias_saturation(q8):
     with open(os.path.join(os.path.dirname(__file__), "golden", "bias_cases.json")) as f:
         cases = json.load(f)["cases"]
