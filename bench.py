@@ -200,6 +200,31 @@ class Layer:
         q8.q8_linear(xq2, self.w_2, self.b_2, g_scale, self.s_2, self.out)
         q8.q8_layernorm_absmax(self.h1f, self.ln_g, self.ln_b, self.x_next, residual=self.out, amax_slots=self.slots_x)
 
+    def step_fused_static(self):
+        """Stored activation scales with the FP32 glue fused: each LayerNorm (and the embedding block) also writes
+        the int8 codes of its output, so QKV and FFN1 have no quantize pass at all.  Call step_fused() once first."""
+        q8 = self.q8
+        M, H, F = self.M, self.H, self.F
+        s = self.s_static
+        if not hasattr(self, "xq_x"):
+            torch = self.torch
+            self.xq_x = torch.empty((M, H), dtype=torch.int8, device="cuda")     # codes of the layer input (previous LayerNorm)
+            self.xq_h = torch.empty((M, H), dtype=torch.int8, device="cuda")
+            self.xq_e = torch.empty((M, H), dtype=torch.int8, device="cuda")
+            q8.q8_quantize(self.x_in, s[0:1], self.xq_x)
+        q8.q8_embedding_sum3_layernorm(self.tables[0], self.tables[1], self.tables[2], self.table_scales, self.ids[0],
+                                       self.ids[1], self.ids[2], self.ln_g, self.ln_b, self.emb, q_scale=s[0:1],
+                                       q_out=self.xq_e, err_flag=self.err)
+        q8.q8_linear(self.xq_x, self.w_qkv, self.b_qkv, s[0:1], self.s_qkv, self.qkv, n_groups=3)
+        xq = self.xq[: M * H].view(M, H)
+        q8.q8_quantize(self.ctx, s[1:2], xq)
+        q8.q8_linear(xq, self.w_o, self.b_o, s[1:2], self.s_o, self.attn_out)
+        q8.q8_layernorm_absmax(self.x_in, self.ln_g, self.ln_b, self.h1f, residual=self.attn_out, q_scale=s[2:3], q_out=self.xq_h)
+        q8.q8_linear(self.xq_h, self.w_1, self.b_1, s[2:3], self.s_1, self.gq, next_scale=s[3:4],
+                     flags=q8.EPI_GELU | q8.EPI_REQUANT)
+        q8.q8_linear(self.gq, self.w_2, self.b_2, s[3:4], self.s_2, self.out)
+        q8.q8_layernorm_absmax(self.h1f, self.ln_g, self.ln_b, self.x_next, residual=self.out, q_scale=s[0:1], q_out=self.xq_x)
+
     def glue_once(self):
         """Untimed fp32 glue (attention, residual, LayerNorm) so every FC sees realistic inputs."""
         torch = self.torch
@@ -348,6 +373,17 @@ def main():
                                    "note": "dynamic scales; adds embedding+LayerNorm and the layer's two residual+LayerNorm "
                                            "passes to the step and drops the abs-max passes of QKV and FFN1 (their abs-max "
                                            "comes out of the LayerNorm kernels)"}
+    for _ in range(5):
+        layer.step_fused_static()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n_static):
+        layer.step_fused_static()
+    torch.cuda.synchronize()
+    dtfs = (time.perf_counter() - t0) / n_static
+    out["fused_layernorm_static_mode"] = {"ms_per_step": round(dtfs * 1e3, 4), "tokens_per_s": round(layer.M / dtfs, 1), "steps": n_static,
+                                          "note": "stored scales; the embedding block and both residual+LayerNorm passes also "
+                                                  "write the int8 codes of their output, so QKV and FFN1 have no quantize pass"}
     # the memory-bound kernels on their own: achieved bytes/s against the 8 TB/s of the HBM (algorithmic bytes)
     def hbm_rate(fn, nbytes, reps=20):
         for _ in range(3):

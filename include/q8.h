@@ -219,13 +219,18 @@ q8_status q8_ste_backward(const float* grad_xq, int64_t n, float* grad_x, void* 
  *     q8_quantize_amax(y, ..., amax_slots, Q8_AMAX_SLOTS, ...) and no abs-max pass is needed.
  *   a fp32[M,H]; residual fp32[M,H] or NULL; gamma, beta fp32[H]; eps host float (BERT: 1e-12).
  *   y fp32[M,H], may be a itself (in place); amax_slots fp32[Q8_AMAX_SLOTS] or NULL.
+ *   q_scale fp32[1] and q_out int8[M,H], both or neither: with a stored activation scale (Eq. 4)
+ *   the same pass also writes q_out = Quantize(y | q_scale[0], 127) (Eq. 1 on the fp32 y it
+ *   stores), i.e. the next FC layer's whole quantizer; y is still written for the FP32 consumers
+ *   (the residual path).
  *   Statistics and normalisation are evaluated in binary64 and rounded once: y is within one
  *   ulp of the exact value.  M >= 0 (M = 0: every slot 0); H >= 1.  Rows with H % 4 == 0,
  *   H <= 2048 and 16-byte aligned pointers stay in registers; others take a slower kernel with
  *   the same results.
  */
 q8_status q8_layernorm_absmax(const float* a, const float* residual, const float* gamma, const float* beta,
-                              float eps, int64_t M, int64_t H, float* y, float* amax_slots, void* stream);
+                              float eps, int64_t M, int64_t H, float* y, float* amax_slots,
+                              const float* q_scale, int8_t* q_out, void* stream);
 
 /*
  * BERT's input block in one pass: the three-table int8 embedding lookup of q8_embedding_sum3
@@ -237,7 +242,8 @@ q8_status q8_embedding_sum3_layernorm(const int8_t* word, int64_t Vw, const int8
                                       const int8_t* type, int64_t Vt, const float* scales, int64_t H,
                                       const int32_t* wid, const int32_t* pid, const int32_t* tid, int64_t T,
                                       const float* gamma, const float* beta, float eps,
-                                      float* y, float* amax_slots, int32_t* err_flag, void* stream);
+                                      float* y, float* amax_slots, const float* q_scale, int8_t* q_out,
+                                      int32_t* err_flag, void* stream);
 
 /* Library version string and a short text for a status code (host pointers, static storage). */
 const char* q8_version(void);

@@ -201,33 +201,37 @@ q8_status q8_ste_backward(const float* grad_xq, int64_t n, float* grad_x, void* 
 }
 
 q8_status q8_layernorm_absmax(const float* a, const float* residual, const float* gamma, const float* beta, float eps,
-                              int64_t M, int64_t H, float* y, float* amax_slots, void* stream)
+                              int64_t M, int64_t H, float* y, float* amax_slots, const float* q_scale, int8_t* q_out,
+                              void* stream)
 {
     if (M < 0 || H < 1 || !(eps >= 0.0f)) return Q8_ERR_SHAPE;
-    if (!gamma || !beta) return Q8_ERR_NULL;
+    if (!gamma || !beta || ((q_scale == nullptr) != (q_out == nullptr))) return Q8_ERR_NULL;
+    if (misaligned(q_scale, 4)) return Q8_ERR_ALIGN;
     if (M > 0 && (!a || !y)) return Q8_ERR_NULL;
     if (misaligned(a, 4) || misaligned(residual, 4) || misaligned(gamma, 4) || misaligned(beta, 4) || misaligned(y, 4) ||
         misaligned(amax_slots, 4))
         return Q8_ERR_ALIGN;
-    return q8::launch_layernorm(a, residual, gamma, beta, eps, M, H, y, amax_slots, as_stream(stream)) ? Q8_ERR_LAUNCH
-                                                                                                        : Q8_OK;
+    return q8::launch_layernorm(a, residual, gamma, beta, eps, M, H, y, amax_slots, q_scale, q_out, as_stream(stream))
+               ? Q8_ERR_LAUNCH
+               : Q8_OK;
 }
 
 q8_status q8_embedding_sum3_layernorm(const int8_t* word, int64_t Vw, const int8_t* pos, int64_t Vp, const int8_t* type,
                                       int64_t Vt, const float* scales, int64_t H, const int32_t* wid,
                                       const int32_t* pid, const int32_t* tid, int64_t T, const float* gamma,
-                                      const float* beta, float eps, float* y, float* amax_slots, int32_t* err_flag,
-                                      void* stream)
+                                      const float* beta, float eps, float* y, float* amax_slots, const float* q_scale,
+                                      int8_t* q_out, int32_t* err_flag, void* stream)
 {
     if (Vw < 0 || Vp < 0 || Vt < 0 || H < 1 || T < 0 || !(eps >= 0.0f)) return Q8_ERR_SHAPE;
-    if (!gamma || !beta || !scales) return Q8_ERR_NULL;
+    if (!gamma || !beta || !scales || ((q_scale == nullptr) != (q_out == nullptr))) return Q8_ERR_NULL;
+    if (misaligned(q_scale, 4)) return Q8_ERR_ALIGN;
     if (T > 0 && (!wid || !pid || !tid || !y)) return Q8_ERR_NULL;
     if (T > 0 && ((Vw > 0 && !word) || (Vp > 0 && !pos) || (Vt > 0 && !type))) return Q8_ERR_NULL;
     if (misaligned(wid, 4) || misaligned(pid, 4) || misaligned(tid, 4) || misaligned(y, 4) || misaligned(scales, 4) ||
         misaligned(err_flag, 4) || misaligned(gamma, 4) || misaligned(beta, 4) || misaligned(amax_slots, 4))
         return Q8_ERR_ALIGN;
     return q8::launch_embedding_sum3_layernorm(word, Vw, pos, Vp, type, Vt, scales, H, wid, pid, tid, T, gamma, beta, eps,
-                                               y, amax_slots, err_flag, as_stream(stream))
+                                               y, amax_slots, q_scale, q_out, err_flag, as_stream(stream))
                ? Q8_ERR_LAUNCH
                : Q8_OK;
 }

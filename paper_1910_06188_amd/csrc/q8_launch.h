@@ -53,12 +53,12 @@ int launch_embedding_sum3(const int8_t* word, int64_t Vw, const int8_t* pos, int
 
 // FP32 glue fused with the abs-max of the next quantizer: LayerNorm of a (+ r), or of the summed embedding rows.
 int launch_layernorm(const float* a, const float* r, const float* gamma, const float* beta, float eps, int64_t M,
-                     int64_t H, float* y, float* amax_slots, hipStream_t st);
+                     int64_t H, float* y, float* amax_slots, const float* q_scale, int8_t* q_out, hipStream_t st);
 int launch_embedding_sum3_layernorm(const int8_t* word, int64_t Vw, const int8_t* pos, int64_t Vp, const int8_t* typ,
                                     int64_t Vt, const float* scales, int64_t H, const int32_t* wid,
                                     const int32_t* pid, const int32_t* tid, int64_t T, const float* gamma,
-                                    const float* beta, float eps, float* y, float* amax_slots, int32_t* err_flag,
-                                    hipStream_t st);
+                                    const float* beta, float eps, float* y, float* amax_slots, const float* q_scale,
+                                    int8_t* q_out, int32_t* err_flag, hipStream_t st);
 
 // Tuning hook used by the benchmark and tests: selects the MFMA tile variant
 // (0 = automatic choice from the shape).

@@ -51,11 +51,14 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_rows_kernel(const float*
                                                                      const float* __restrict__ gamma,
                                                                      const float* __restrict__ beta, double eps,
                                                                      int64_t M, int H, float* y,
-                                                                     unsigned* __restrict__ amax_slots)
+                                                                     unsigned* __restrict__ amax_slots,
+                                                                     const float* __restrict__ q_scale,
+                                                                     unsigned* __restrict__ q_out)
 {
     __shared__ unsigned wave_amax[kLnThreads / 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nvec = H >> 2;
+    const float qs = q_out ? q_scale[0] : 0.0f;
     float amax = 0.0f;
     float r0 = 0.f, r1 = 0.f, r2 = 0.f;
     if (kSrc == 2) {
@@ -126,6 +129,9 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_rows_kernel(const float*
                 o.z = (float)(((double)x[j].z - mean) * rstd * (double)g.z + (double)b.z);
                 o.w = (float)(((double)x[j].w - mean) * rstd * (double)g.w + (double)b.w);
                 yv[v] = o;
+                if (q_out)  // stored-scale quantizer of the next FC (Eq. 1 on the rounded fp32 value), 4 codes per lane
+                    q_out[row * nvec + v] = ((unsigned)quantize_code(o.x, qs) & 0xffu) | (((unsigned)quantize_code(o.y, qs) & 0xffu) << 8) |
+                                            (((unsigned)quantize_code(o.z, qs) & 0xffu) << 16) | ((unsigned)quantize_code(o.w, qs) << 24);
                 amax = __builtin_fmaxf(amax, __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(o.x), __builtin_fabsf(o.y)),
                                                             __builtin_fmaxf(__builtin_fabsf(o.z), __builtin_fabsf(o.w))));
             }
@@ -154,11 +160,14 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_generic_kernel(const flo
                                                                         const float* __restrict__ gamma,
                                                                         const float* __restrict__ beta, double eps,
                                                                         int64_t M, int64_t H, float* y,
-                                                                        unsigned* __restrict__ amax_slots)
+                                                                        unsigned* __restrict__ amax_slots,
+                                                                        const float* __restrict__ q_scale,
+                                                                        int8_t* __restrict__ q_out)
 {
     __shared__ unsigned wave_amax[kLnThreads / 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     float amax = 0.0f;
+    const float qs = q_out ? q_scale[0] : 0.0f;
     float r0 = 0.f, r1 = 0.f, r2 = 0.f;
     if (kSrc == 2) {
         r0 = __fdiv_rn(1.0f, es.scales[0]);
@@ -196,6 +205,7 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_generic_kernel(const flo
         for (int64_t h = lane; h < H; h += 64) {
             const float o = (float)(((double)value(h) - mean) * rstd * (double)gamma[h] + (double)beta[h]);
             y[row * H + h] = o;
+            if (q_out) q_out[row * H + h] = (int8_t)quantize_code(o, qs);
             amax = __builtin_fmaxf(amax, __builtin_fabsf(o));
         }
     }
@@ -227,7 +237,7 @@ static int ln_grid(int64_t M)
 }
 
 int launch_layernorm(const float* a, const float* r, const float* gamma, const float* beta, float eps, int64_t M,
-                     int64_t H, float* y, float* amax_slots, hipStream_t st)
+                     int64_t H, float* y, float* amax_slots, const float* q_scale, int8_t* q_out, hipStream_t st)
 {
     unsigned* slots = reinterpret_cast<unsigned*>(amax_slots);
     if (M == 0) {
@@ -236,22 +246,22 @@ int launch_layernorm(const float* a, const float* r, const float* gamma, const f
     }
     EmbedSrc es = {};
     const bool fast = H % 4 == 0 && H <= 64 * 4 * kLnMaxVec && aligned16(a) && aligned16(y) && aligned16(gamma) &&
-                      aligned16(beta) && (!r || aligned16(r));
+                      aligned16(beta) && (!r || aligned16(r)) && (reinterpret_cast<uintptr_t>(q_out) & 3) == 0;
     const dim3 grid(ln_grid(M)), block(kLnThreads);
     if (fast) {
         if (r)
             hipLaunchKernelGGL(layernorm_rows_kernel<1>, grid, block, 0, st, a, r, es, gamma, beta, (double)eps, M,
-                               (int)H, y, slots);
+                               (int)H, y, slots, q_scale, reinterpret_cast<unsigned*>(q_out));
         else
             hipLaunchKernelGGL(layernorm_rows_kernel<0>, grid, block, 0, st, a, r, es, gamma, beta, (double)eps, M,
-                               (int)H, y, slots);
+                               (int)H, y, slots, q_scale, reinterpret_cast<unsigned*>(q_out));
     } else {
         if (r)
             hipLaunchKernelGGL(layernorm_generic_kernel<1>, grid, block, 0, st, a, r, es, nullptr, nullptr, nullptr,
-                               gamma, beta, (double)eps, M, H, y, slots);
+                               gamma, beta, (double)eps, M, H, y, slots, q_scale, q_out);
         else
             hipLaunchKernelGGL(layernorm_generic_kernel<0>, grid, block, 0, st, a, r, es, nullptr, nullptr, nullptr,
-                               gamma, beta, (double)eps, M, H, y, slots);
+                               gamma, beta, (double)eps, M, H, y, slots, q_scale, q_out);
     }
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
@@ -259,8 +269,8 @@ int launch_layernorm(const float* a, const float* r, const float* gamma, const f
 int launch_embedding_sum3_layernorm(const int8_t* word, int64_t Vw, const int8_t* pos, int64_t Vp, const int8_t* typ,
                                     int64_t Vt, const float* scales, int64_t H, const int32_t* wid,
                                     const int32_t* pid, const int32_t* tid, int64_t T, const float* gamma,
-                                    const float* beta, float eps, float* y, float* amax_slots, int32_t* err_flag,
-                                    hipStream_t st)
+                                    const float* beta, float eps, float* y, float* amax_slots, const float* q_scale,
+                                    int8_t* q_out, int32_t* err_flag, hipStream_t st)
 {
     unsigned* slots = reinterpret_cast<unsigned*>(amax_slots);
     if (T == 0) {
@@ -277,14 +287,14 @@ int launch_embedding_sum3_layernorm(const int8_t* word, int64_t Vw, const int8_t
     es.err_flag = err_flag;
     const auto a4 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3) == 0; };
     const bool fast = H % 4 == 0 && H <= 64 * 4 * kLnMaxVec && a4(word) && a4(pos) && a4(typ) && aligned16(y) &&
-                      aligned16(gamma) && aligned16(beta);
+                      aligned16(gamma) && aligned16(beta) && a4(q_out);
     const dim3 grid(ln_grid(T)), block(kLnThreads);
     if (fast)
         hipLaunchKernelGGL(layernorm_rows_kernel<2>, grid, block, 0, st, nullptr, nullptr, es, gamma, beta,
-                           (double)eps, T, (int)H, y, slots);
+                           (double)eps, T, (int)H, y, slots, q_scale, reinterpret_cast<unsigned*>(q_out));
     else
         hipLaunchKernelGGL(layernorm_generic_kernel<2>, grid, block, 0, st, nullptr, nullptr, es, word, pos, typ, gamma,
-                           beta, (double)eps, T, H, y, slots);
+                           beta, (double)eps, T, H, y, slots, q_scale, q_out);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 

@@ -43,9 +43,9 @@ _lib.q8_fake_quantize.argtypes = [_vp, _i64, _vp, _vp, _vp]
 _lib.q8_ema_update.argtypes = [_vp, _i32, _f32, _vp, _vp, _vp, _vp]
 _lib.q8_fake_quantize_ema.argtypes = [_vp, _i64, _f32, _vp, _vp, _vp, _vp]
 _lib.q8_ste_backward.argtypes = [_vp, _i64, _vp, _vp]
-_lib.q8_layernorm_absmax.argtypes = [_vp, _vp, _vp, _vp, _f32, _i64, _i64, _vp, _vp, _vp]
+_lib.q8_layernorm_absmax.argtypes = [_vp, _vp, _vp, _vp, _f32, _i64, _i64, _vp, _vp, _vp, _vp, _vp]
 _lib.q8_embedding_sum3_layernorm.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _f32,
-                                             _vp, _vp, _vp, _vp]
+                                             _vp, _vp, _vp, _vp, _vp, _vp]
 for _f in ("q8_layernorm_absmax", "q8_embedding_sum3_layernorm", "q8_fake_quantize", "q8_ema_update", "q8_fake_quantize_ema", "q8_ste_backward", "q8_absmax", "q8_scale_from_amax", "q8_quantize", "q8_quantize_amax", "q8_linear", "q8_linear_f32", "q8_embedding",
            "q8_embedding_sum3"):
     getattr(_lib, _f).restype = C.c_int
@@ -196,19 +196,23 @@ def q8_ste_backward(grad_xq, grad_x, stream=None) -> None:
     _ck(_lib.q8_ste_backward(_ptr(grad_xq), grad_xq.numel(), _ptr(grad_x), _stream(stream)), "q8_ste_backward")
 
 
-def q8_layernorm_absmax(a, gamma, beta, y, eps=1e-12, residual=None, amax_slots=None, stream=None) -> None:
-    """y = LayerNorm(a (+ residual)) * gamma + beta, plus abs-max slots of y for the next quantizer."""
+def q8_layernorm_absmax(a, gamma, beta, y, eps=1e-12, residual=None, amax_slots=None, q_scale=None, q_out=None,
+                        stream=None) -> None:
+    """y = LayerNorm(a (+ residual)) * gamma + beta, plus abs-max slots of y for the next quantizer, or
+    (stored scale) the int8 codes of y themselves."""
     M, H = a.shape
     if y.numel() != M * H or gamma.numel() != H or beta.numel() != H or (residual is not None and residual.numel() != M * H):
         raise ValueError("q8_layernorm_absmax: shape mismatch")
     if amax_slots is not None and amax_slots.numel() < AMAX_SLOTS:
         raise ValueError("q8_layernorm_absmax: amax_slots holds AMAX_SLOTS floats")
+    if q_out is not None and q_out.numel() != M * H:
+        raise ValueError("q8_layernorm_absmax: q_out and y differ in size")
     _ck(_lib.q8_layernorm_absmax(_ptr(a), _ptr(residual), _ptr(gamma), _ptr(beta), float(eps), M, H, _ptr(y),
-                                 _ptr(amax_slots), _stream(stream)), "q8_layernorm_absmax")
+                                 _ptr(amax_slots), _ptr(q_scale), _ptr(q_out), _stream(stream)), "q8_layernorm_absmax")
 
 
 def q8_embedding_sum3_layernorm(word, pos, typ, scales, wid, pid, tid, gamma, beta, y, eps=1e-12, amax_slots=None,
-                                err_flag=None, stream=None) -> None:
+                                q_scale=None, q_out=None, err_flag=None, stream=None) -> None:
     """Three-table int8 lookup, sum, LayerNorm and abs-max slots in one pass."""
     H = word.shape[1]
     T = wid.numel()
@@ -218,7 +222,8 @@ def q8_embedding_sum3_layernorm(word, pos, typ, scales, wid, pid, tid, gamma, be
         raise ValueError("q8_embedding_sum3_layernorm: parameter size mismatch")
     _ck(_lib.q8_embedding_sum3_layernorm(_ptr(word), word.shape[0], _ptr(pos), pos.shape[0], _ptr(typ), typ.shape[0],
                                          _ptr(scales), H, _ptr(wid), _ptr(pid), _ptr(tid), T, _ptr(gamma), _ptr(beta),
-                                         float(eps), _ptr(y), _ptr(amax_slots), _ptr(err_flag), _stream(stream)),
+                                         float(eps), _ptr(y), _ptr(amax_slots), _ptr(q_scale), _ptr(q_out), _ptr(err_flag),
+                                         _stream(stream)),
         "q8_embedding_sum3_layernorm")
 
 

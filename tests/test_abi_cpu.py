@@ -90,16 +90,17 @@ def test_host_side_argument_checks(lib):
     assert lib.q8_ste_backward(p, -2, p, None) == SHAPE
     assert lib.q8_ste_backward(p, 0, None, None) == OK
     # fused LayerNorm entry points
-    lib.q8_layernorm_absmax.argtypes = [vp, vp, vp, vp, C.c_float, i64, i64, vp, vp, vp]
-    lib.q8_embedding_sum3_layernorm.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, vp, vp, vp, i64, vp, vp, C.c_float, vp, vp, vp, vp]
-    assert lib.q8_layernorm_absmax(p, None, p, p, 1e-12, -1, 4, p, None, None) == SHAPE
-    assert lib.q8_layernorm_absmax(p, None, p, p, 1e-12, 4, 0, p, None, None) == SHAPE
-    assert lib.q8_layernorm_absmax(p, None, p, p, -1.0, 4, 4, p, None, None) == SHAPE
-    assert lib.q8_layernorm_absmax(None, None, p, p, 1e-12, 4, 4, p, None, None) == NULL
-    assert lib.q8_layernorm_absmax(p, None, None, p, 1e-12, 4, 4, p, None, None) == NULL
-    assert lib.q8_layernorm_absmax(p + 2, None, p, p, 1e-12, 1, 4, p, None, None) == ALIGN
-    assert lib.q8_embedding_sum3_layernorm(p, 4, p, 4, p, 4, p, 4, None, p, p, 2, p, p, 1e-12, p, None, None, None) == NULL
-    assert lib.q8_embedding_sum3_layernorm(p, 4, p, 4, p, 4, p, 0, p, p, p, 2, p, p, 1e-12, p, None, None, None) == SHAPE
+    lib.q8_layernorm_absmax.argtypes = [vp, vp, vp, vp, C.c_float, i64, i64, vp, vp, vp, vp, vp]
+    lib.q8_embedding_sum3_layernorm.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, vp, vp, vp, i64, vp, vp, C.c_float, vp, vp, vp, vp, vp, vp]
+    assert lib.q8_layernorm_absmax(p, None, p, p, 1e-12, -1, 4, p, None, None, None, None) == SHAPE
+    assert lib.q8_layernorm_absmax(p, None, p, p, 1e-12, 4, 0, p, None, None, None, None) == SHAPE
+    assert lib.q8_layernorm_absmax(p, None, p, p, -1.0, 4, 4, p, None, None, None, None) == SHAPE
+    assert lib.q8_layernorm_absmax(None, None, p, p, 1e-12, 4, 4, p, None, None, None, None) == NULL
+    assert lib.q8_layernorm_absmax(p, None, p, p, 1e-12, 4, 4, p, None, p, None, None) == NULL      # scale without codes
+    assert lib.q8_layernorm_absmax(p, None, None, p, 1e-12, 4, 4, p, None, None, None, None) == NULL
+    assert lib.q8_layernorm_absmax(p + 2, None, p, p, 1e-12, 1, 4, p, None, None, None, None) == ALIGN
+    assert lib.q8_embedding_sum3_layernorm(p, 4, p, 4, p, 4, p, 4, None, p, p, 2, p, p, 1e-12, p, None, None, None, None, None) == NULL
+    assert lib.q8_embedding_sum3_layernorm(p, 4, p, 4, p, 4, p, 0, p, p, p, 2, p, p, 1e-12, p, None, None, None, None, None) == SHAPE
 
 
 def test_product_package_does_not_reach_the_oracle():

@@ -62,6 +62,14 @@ def test_layernorm_absmax(q8, M, H, with_residual):
     q8.q8_quantize_amax(y, slots, sc, q, amax_out=am)
     assert host(am)[0] == np.abs(got).max() and host(sc)[0] == O.scale(np.abs(got).max())
     np.testing.assert_array_equal(host(q), O.quantize(got, host(sc)[0]))
+    # stored scale: the same pass writes the codes of its own y (and the same y)
+    qs = np.float32(127.0) / np.float32(4.0)
+    y2 = torch.empty((M, H), device="cuda")
+    q2 = torch.full((M, H), 99, dtype=torch.int8, device="cuda")
+    q8.q8_layernorm_absmax(dev(a), dev(gamma), dev(beta), y2, eps=1e-12, residual=None if r is None else dev(r),
+                           q_scale=torch.tensor([float(qs)], device="cuda"), q_out=q2)
+    np.testing.assert_array_equal(host(y2), got)
+    np.testing.assert_array_equal(host(q2), O.quantize(got, qs))
     # without slots, and in place
     ad = dev(a)
     q8.q8_layernorm_absmax(ad, dev(gamma), dev(beta), ad, eps=1e-12, residual=None if r is None else dev(r))
@@ -127,6 +135,14 @@ def test_embedding_sum3_layernorm(q8, T, H, V):
     mag = (np.abs(q["word"][wid].astype(np.float64)) / float(s["word"]) + np.abs(q["position"][pid].astype(np.float64)) / float(s["position"])
            + np.abs(q["token_type"][tid].astype(np.float64)) / float(s["token_type"]))     # three fp32 terms: tolerance scaled by their sizes
     assert np.all(np.abs(host(summed).astype(np.float64) - emb) <= 1e-6 * mag + 1e-12)
+    # stored scale: codes of the same y in the same pass
+    qs = np.float32(127.0) / np.float32(4.5)
+    qo = torch.empty((T, H), dtype=torch.int8, device="cuda")
+    y3 = torch.empty((T, H), device="cuda")
+    q8.q8_embedding_sum3_layernorm(*args, dev(wid), dev(pid), dev(tid), dev(gamma), dev(beta), y3, eps=1e-12,
+                                   q_scale=torch.tensor([float(qs)], device="cuda"), q_out=qo, err_flag=err)
+    np.testing.assert_array_equal(host(y3), got)
+    np.testing.assert_array_equal(host(qo), O.quantize(got, qs))
     # a bad id: zero row -> beta, flag raised, nothing else disturbed
     wid_bad = wid.copy()
     wid_bad[T // 2] = V
@@ -141,12 +157,12 @@ def test_layernorm_argument_checks(q8):
     lib = q8.raw()
     x = torch.zeros(16, device="cuda")
     p = x.data_ptr()
-    assert lib.q8_layernorm_absmax(p, None, p, p, 1e-12, -1, 4, p, None, None) == 2
-    assert lib.q8_layernorm_absmax(p, None, p, p, 1e-12, 4, 0, p, None, None) == 2
-    assert lib.q8_layernorm_absmax(p, None, p, p, -1.0, 4, 4, p, None, None) == 2
-    assert lib.q8_layernorm_absmax(None, None, p, p, 1e-12, 4, 4, p, None, None) == 1
-    assert lib.q8_layernorm_absmax(p, None, None, p, 1e-12, 4, 4, p, None, None) == 1
-    assert lib.q8_layernorm_absmax(p + 2, None, p, p, 1e-12, 1, 4, p, None, None) == 3
-    assert lib.q8_embedding_sum3_layernorm(p, 4, p, 4, p, 4, p, 4, None, p, p, 2, p, p, 1e-12, p, None, None, None) == 1
-    assert lib.q8_embedding_sum3_layernorm(p, 4, p, 4, p, 4, p, 0, p, p, p, 2, p, p, 1e-12, p, None, None, None) == 2
+    assert lib.q8_layernorm_absmax(p, None, p, p, 1e-12, -1, 4, p, None, None, None, None) == 2
+    assert lib.q8_layernorm_absmax(p, None, p, p, 1e-12, 4, 0, p, None, None, None, None) == 2
+    assert lib.q8_layernorm_absmax(p, None, p, p, -1.0, 4, 4, p, None, None, None, None) == 2
+    assert lib.q8_layernorm_absmax(None, None, p, p, 1e-12, 4, 4, p, None, None, None, None) == 1
+    assert lib.q8_layernorm_absmax(p, None, None, p, 1e-12, 4, 4, p, None, None, None, None) == 1
+    assert lib.q8_layernorm_absmax(p + 2, None, p, p, 1e-12, 1, 4, p, None, None, None, None) == 3
+    assert lib.q8_embedding_sum3_layernorm(p, 4, p, 4, p, 4, p, 4, None, p, p, 2, p, p, 1e-12, p, None, None, None, None, None) == 1
+    assert lib.q8_embedding_sum3_layernorm(p, 4, p, 4, p, 4, p, 0, p, p, p, 2, p, p, 1e-12, p, None, None, None, None, None) == 2
     torch.cuda.synchronize()
