@@ -183,3 +183,34 @@ def test_operand_beyond_2_gib(q8):
             assert np.all(np.abs(got.astype(np.float64) - y_ref) <= 1e-6 * np.abs(y_ref.astype(np.float64))), variant
         finally:
             q8.set_gemm_variant(0)
+
+
+def test_elementwise_beyond_2_31_elements(q8):
+    """abs-max and quantize on 2^31 + 4099 floats (8.6 GB): element indices do not fit 32 bits.  The
+    extreme value sits past the 2^31-th element; every code is compared with the oracle."""
+    n = (1 << 31) + 4099
+    g = synth.rng(79)
+    block = g.standard_normal(1 << 24, dtype=np.float32)
+    x = np.tile(block, (n + block.size - 1) // block.size)[:n]
+    x[n - 7] = np.float32(-9.75)                                  # the abs-max, beyond index 2^31
+    x[(1 << 31) + 1] = np.float32(9.5)
+    xd = torch.from_numpy(x).cuda()
+    amax, sc = one(), one()
+    q8.q8_absmax(xd, amax, sc)
+    assert amax.item() == 9.75 and sc.item() == float(O.scale(np.float32(9.75)))
+    q = torch.empty(n, dtype=torch.int8, device="cuda")
+    q8.q8_quantize(xd, sc, q)
+    qh = q.cpu().numpy()
+    ref = O.quantize(x, O.scale(np.float32(9.75)))
+    assert qh[n - 7] == -127 and np.array_equal(qh, ref)
+    # the fused form (partial maxima folded by the quantize kernel) on the same tensor
+    scal = torch.zeros(q8.SCAL_WORK, device="cuda")
+    q.zero_()
+    y = torch.empty((1, 1), device="cuda")
+    w1 = torch.ones((1, 1), dtype=torch.int8, device="cuda")
+    lib = q8.raw()
+    rc = lib.q8_linear_f32(xd.data_ptr(), w1.data_ptr(), None, sc.data_ptr(), 1, n, 1, 1, q.data_ptr(), scal.data_ptr(),
+                           torch.empty((n, 1), device="cuda").data_ptr(), None, None, None, 0, None)
+    assert rc == 0
+    torch.cuda.synchronize()
+    assert scal[0].item() == 9.75 and np.array_equal(q.cpu().numpy(), ref)
