@@ -244,6 +244,18 @@ __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM*
 
     v4i fa[2][FM], fb[2][FN];  // fragments of the current / next k-step, double buffered in registers
 
+    // The epilogue's per-column inputs (activation scale, weight scale of the column's group, bias)
+    // are fetched now and only used after the main loop: fetched there, their latency would sit
+    // between the last MFMA and the first store of every tile.
+    const float sx = ep.sx[0];
+    float sw_col[FN], bias_col[FN];
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+        const int n = min(n0 + wn * TN + j * 32 + l32, N - 1);
+        sw_col[j] = ep.sw[n / ep.cols_per_group];
+        bias_col[j] = ep.bias ? ep.bias[n] : 0.0f;
+    }
+
     // Prologue: stages 0 and 1 of both operands; wait for stage 0.
     load_all_a(src_a(0, 0));
     load_all_b(src_b(0, 0));
@@ -335,7 +347,6 @@ __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM*
 
     // Epilogue.  Accumulator register e of lane l is row 8*(e/4) + 4*(l/32) + e%4 and
     // column l%32 of its 32x32 block: 32 lanes store 128 contiguous bytes of one row.
-    const float sx = ep.sx[0];
     float next_scale = 0.0f;
     if (do_req) next_scale = ep.next_scale[0];
     unsigned amax = 0u;
@@ -366,7 +377,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM*
         static_for<0, FN>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
             const int n = n0 + wn * TN + j * 32 + l32;
-            const ColConst cc = col_const(ep, n, sx);
+            const ColConst cc = ColConst{ep.bias ? quantize_bias(bias_col[j], sx, sw_col[j]) : 0, dequant_factor(sx, sw_col[j])};
             const int elem0 = row0 * N + n;
             static_for<0, FM>([&](auto ic) {
                 constexpr int i = decltype(ic)::value;
@@ -401,7 +412,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM*
             constexpr int j = decltype(jc)::value;
             const int n = n0 + wn * TN + j * 32 + l32;
             if (n < N) {
-                const ColConst cc = col_const(ep, n, sx);
+                const ColConst cc = ColConst{ep.bias ? quantize_bias(bias_col[j], sx, sw_col[j]) : 0, dequant_factor(sx, sw_col[j])};
                 static_for<0, FM>([&](auto ic) {
                     constexpr int i = decltype(ic)::value;
                     const int mb = m0 + wm * TM + i * 32 + 4 * hi;
