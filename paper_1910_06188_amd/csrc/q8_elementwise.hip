@@ -156,13 +156,26 @@ __global__ __launch_bounds__(kEwThreads) void quantize_amax_kernel(const float* 
                                                                     float* amax_out, float* scale_out,
                                                                     int8_t* __restrict__ q, float* zero_slot)
 {
-    const float s = scale_from_partials(amax, n_amax, amax_out, scale_out, zero_slot);
     const int64_t stride = (int64_t)gridDim.x * kEwThreads;
     int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x;
     if (kVec) {
         const float4* xv = reinterpret_cast<const float4*>(x);
         unsigned* qv = reinterpret_cast<unsigned*>(q);
         const int64_t nvec = n >> 2;
+        // The first trip's loads are requested before the partial maxima are folded: most workgroups
+        // only make one or two trips, so the fold would otherwise sit in front of nearly all the work.
+        float4 first[kEwUnroll];
+        const bool full_first = i + (kEwUnroll - 1) * stride < nvec;
+        if (full_first) {
+#pragma unroll
+            for (int u = 0; u < kEwUnroll; ++u) first[u] = xv[i + u * stride];
+        }
+        const float s = scale_from_partials(amax, n_amax, amax_out, scale_out, zero_slot);
+        if (full_first) {
+#pragma unroll
+            for (int u = 0; u < kEwUnroll; ++u) qv[i + u * stride] = pack4(first[u], s);
+            i += kEwUnroll * stride;
+        }
         for (; i + (kEwUnroll - 1) * stride < nvec; i += kEwUnroll * stride) {
             float4 v[kEwUnroll];
 #pragma unroll
@@ -176,6 +189,7 @@ __global__ __launch_bounds__(kEwThreads) void quantize_amax_kernel(const float* 
             if (t < n) q[t] = (int8_t)quantize_code(x[t], s);
         }
     } else {
+        const float s = scale_from_partials(amax, n_amax, amax_out, scale_out, zero_slot);
         for (; i < n; i += stride) q[i] = (int8_t)quantize_code(x[i], s);
     }
 }
