@@ -87,7 +87,7 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_rows_kernel(const float*
             }
         } else {
             const float4* av = reinterpret_cast<const float4*>(a) + row * nvec;
-            const float4* rv = reinterpret_cast<const float4*>(r) + row * nvec;
+            const float4* rv = kSrc == 1 ? reinterpret_cast<const float4*>(r) + row * nvec : nullptr;
 #pragma unroll
             for (int j = 0; j < kLnMaxVec; ++j) {
                 const int v = j * 64 + lane;
