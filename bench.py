@@ -384,6 +384,40 @@ def main():
     out["fused_layernorm_static_mode"] = {"ms_per_step": round(dtfs * 1e3, 4), "tokens_per_s": round(layer.M / dtfs, 1), "steps": n_static,
                                           "note": "stored scales; the embedding block and both residual+LayerNorm passes also "
                                                   "write the int8 codes of their output, so QKV and FFN1 have no quantize pass"}
+    # the two FFN GEMMs on their own, launched back to back: once on one set of buffers (operands and output stay in
+    # the caches) and once rotating through sets that together exceed the 256 MB Infinity Cache
+    def gemm_alone(N, K, flags, int8_out):
+        per_set = layer.M * K + N * K + (1 if int8_out else 4) * layer.M * N
+        R = int(1.0e9 // per_set) + 2
+        sets = [(torch.randint(-127, 128, (layer.M, K), dtype=torch.int8, device="cuda"),
+                 torch.randint(-127, 128, (N, K), dtype=torch.int8, device="cuda"),
+                 torch.empty((layer.M, N), dtype=torch.int8 if int8_out else torch.float32, device="cuda")) for _ in range(R)]
+        bb = torch.zeros(N, device="cuda")
+        sc = torch.tensor([24.0, 1200.0, 20.0, 0.0], device="cuda")
+        res = {}
+        for mode in ("cache_warm", "rotating"):
+            def launch(i):
+                xq_, wq_, y_ = sets[i % R] if mode == "rotating" else sets[0]
+                q8.q8_linear(xq_, wq_, bb, sc[0:1], sc[1:2], y_, out_amax=sc[3:4] if flags & 2 else None,
+                             next_scale=sc[2:3] if flags & 4 else None, flags=flags)
+            for i in range(R + 2):
+                launch(i)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            n = 4 * R
+            a.record()
+            for i in range(n):
+                launch(i)
+            b.record()
+            torch.cuda.synchronize()
+            us = a.elapsed_time(b) * 1e3 / n
+            res[mode] = {"us": round(us, 1), "int8_tops": round(2.0 * layer.M * N * K / us / 1e6, 1)}
+        return res
+    out["gemm_alone"] = {
+        "FFN2 12288x1024x4096 fp32 out": gemm_alone(layer.H, layer.F, 0, False),
+        "FFN1 12288x4096x1024 fp32 out": gemm_alone(layer.F, layer.H, 0, False),
+        "FFN1 12288x4096x1024 GELU + requantize, int8 out": gemm_alone(layer.F, layer.H, 5, True),
+    }
     # the memory-bound kernels on their own: achieved bytes/s against the 8 TB/s of the HBM (algorithmic bytes)
     def hbm_rate(fn, nbytes, reps=20):
         for _ in range(3):
