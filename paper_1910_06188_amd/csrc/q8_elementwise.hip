@@ -150,7 +150,16 @@ __device__ __forceinline__ float scale_from_partials(const float* __restrict__ a
     return s;
 }
 
-template <bool kVec>
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_f4_nt(const float4* p)
+{
+    const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+
+// kStream: x is larger than a quarter of the Infinity Cache and this is its last reader (its abs-max came
+// from elsewhere), so it is read with the non-temporal hint and does not push the next kernels' inputs out.
+template <bool kVec, bool kStream>
 __global__ __launch_bounds__(kEwThreads) void quantize_amax_kernel(const float* __restrict__ x, int64_t n,
                                                                     const float* __restrict__ amax, int n_amax,
                                                                     float* amax_out, float* scale_out,
@@ -168,7 +177,7 @@ __global__ __launch_bounds__(kEwThreads) void quantize_amax_kernel(const float* 
         const bool full_first = i + (kEwUnroll - 1) * stride < nvec;
         if (full_first) {
 #pragma unroll
-            for (int u = 0; u < kEwUnroll; ++u) first[u] = xv[i + u * stride];
+            for (int u = 0; u < kEwUnroll; ++u) first[u] = kStream ? load_f4_nt(&xv[i + u * stride]) : xv[i + u * stride];
         }
         const float s = scale_from_partials(amax, n_amax, amax_out, scale_out, zero_slot);
         if (full_first) {
@@ -179,7 +188,7 @@ __global__ __launch_bounds__(kEwThreads) void quantize_amax_kernel(const float* 
         for (; i + (kEwUnroll - 1) * stride < nvec; i += kEwUnroll * stride) {
             float4 v[kEwUnroll];
 #pragma unroll
-            for (int u = 0; u < kEwUnroll; ++u) v[u] = xv[i + u * stride];
+            for (int u = 0; u < kEwUnroll; ++u) v[u] = kStream ? load_f4_nt(&xv[i + u * stride]) : xv[i + u * stride];
 #pragma unroll
             for (int u = 0; u < kEwUnroll; ++u) qv[i + u * stride] = pack4(v[u], s);
         }
@@ -358,12 +367,16 @@ int launch_quantize_amax(const float* x, int64_t n, const float* amax, int n_ama
                          int8_t* q, float* zero_slot, hipStream_t st)
 {
     bool vec = ((reinterpret_cast<uintptr_t>(x) & 15) == 0) && ((reinterpret_cast<uintptr_t>(q) & 3) == 0);
-    if (vec)
-        hipLaunchKernelGGL(quantize_amax_kernel<true>, dim3(ew_grid(n >> 2)), dim3(kEwThreads), 0, st, x, n, amax,
+    const bool stream = n * 4 > ((int64_t)64 << 20) && n_amax == 1;  // one abs-max value: it was not made by a pass over x
+    if (vec && stream)
+        hipLaunchKernelGGL((quantize_amax_kernel<true, true>), dim3(ew_grid(n >> 2)), dim3(kEwThreads), 0, st, x, n, amax,
+                           n_amax, amax_out, scale_out, q, zero_slot);
+    else if (vec)
+        hipLaunchKernelGGL((quantize_amax_kernel<true, false>), dim3(ew_grid(n >> 2)), dim3(kEwThreads), 0, st, x, n, amax,
                            n_amax, amax_out, scale_out, q, zero_slot);
     else
-        hipLaunchKernelGGL(quantize_amax_kernel<false>, dim3(ew_grid(n)), dim3(kEwThreads), 0, st, x, n, amax, n_amax,
-                           amax_out, scale_out, q, zero_slot);
+        hipLaunchKernelGGL((quantize_amax_kernel<false, false>), dim3(ew_grid(n)), dim3(kEwThreads), 0, st, x, n, amax,
+                           n_amax, amax_out, scale_out, q, zero_slot);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
