@@ -587,6 +587,13 @@ def test_quantize_amax_one_value_and_partials(q8):
         q8.q8_quantize_amax(dev(x), dev(np.array(amax_vals, np.float32)), scale_out, q, amax_out=amax_out)
         assert host(scale_out)[0] == s and host(amax_out)[0] == a
         np.testing.assert_array_equal(host(q), O.quantize(x, s))
+    # a tensor above 64 MB with a single abs-max value: the streaming (non-temporal load) form of the kernel
+    big = np.tile(x, 170)[: 17_000_003]
+    qb = torch.empty(big.size, dtype=torch.int8, device="cuda")
+    scale_out = scalar(-1.0)
+    q8.q8_quantize_amax(dev(big), dev(np.array([float(a)], np.float32)), scale_out, qb)
+    assert host(scale_out)[0] == s
+    np.testing.assert_array_equal(host(qb), O.quantize(big, s))
     # all-zero abs-max: S = 1; misaligned views take the scalar kernel
     scale_out = scalar(-1.0)
     q = torch.empty(16, dtype=torch.int8, device="cuda")
