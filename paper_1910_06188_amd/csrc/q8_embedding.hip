@@ -66,7 +66,10 @@ __global__ __launch_bounds__(256) void embedding_scalar_kernel(const int8_t* __r
 }
 
 // word + position + token-type rows, each dequantised with its own scale, summed as
-// (word + position) + type in fp32.  A token row per workgroup at a time.  Needs H % 4 == 0.
+// (word + position) + type in fp32.  A workgroup takes kRows token rows per trip: their ids are
+// fetched first, then all their table rows, then the sums are stored -- one row at a time the
+// kernel was bound by the id -> row -> store latency chain, not by bandwidth.  Needs H % 4 == 0.
+constexpr int kEmbRows = 4;
 __global__ __launch_bounds__(256) void embedding_sum3_kernel(const unsigned* __restrict__ word, int64_t Vw,
                                                               const unsigned* __restrict__ pos, int64_t Vp,
                                                               const unsigned* __restrict__ typ, int64_t Vt,
@@ -77,25 +80,43 @@ __global__ __launch_bounds__(256) void embedding_sum3_kernel(const unsigned* __r
                                                               float4* __restrict__ out, int32_t* err_flag)
 {
     const float r0 = __fdiv_rn(1.0f, scales[0]), r1 = __fdiv_rn(1.0f, scales[1]), r2 = __fdiv_rn(1.0f, scales[2]);
-    for (int64_t t = blockIdx.x; t < T; t += gridDim.x) {  // ids are wave-uniform: scalar loads
-        const int64_t a = wid[t], b = pid[t], c = tid[t];
-        const bool ok = a >= 0 && a < Vw && b >= 0 && b < Vp && c >= 0 && c < Vt;
-        if (!ok && err_flag && threadIdx.x == 0) err_flag[0] = 1;
-        const unsigned* wr = word + (ok ? a : 0) * H4;
-        const unsigned* pr = pos + (ok ? b : 0) * H4;
-        const unsigned* tr = typ + (ok ? c : 0) * H4;
+    for (int64_t t0 = (int64_t)blockIdx.x * kEmbRows; t0 < T; t0 += (int64_t)gridDim.x * kEmbRows) {
+        const unsigned *wr[kEmbRows], *pr[kEmbRows], *tr[kEmbRows];
+        bool ok[kEmbRows];
+#pragma unroll
+        for (int r = 0; r < kEmbRows; ++r) {  // ids are wave-uniform: scalar loads
+            const int64_t t = min(t0 + r, T - 1);
+            const int64_t a = wid[t], b = pid[t], c = tid[t];
+            ok[r] = a >= 0 && a < Vw && b >= 0 && b < Vp && c >= 0 && c < Vt;
+            if (!ok[r] && err_flag && threadIdx.x == 0) err_flag[0] = 1;
+            wr[r] = word + (ok[r] ? a : 0) * H4;
+            pr[r] = pos + (ok[r] ? b : 0) * H4;
+            tr[r] = typ + (ok[r] ? c : 0) * H4;
+        }
         for (int j = threadIdx.x; j < H4; j += 256) {
-            float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (ok) {
-                const float4 x = dequant4(wr[j], r0);
-                const float4 y = dequant4(pr[j], r1);
-                const float4 z = dequant4(tr[j], r2);
-                o.x = (x.x + y.x) + z.x;
-                o.y = (x.y + y.y) + z.y;
-                o.z = (x.z + y.z) + z.z;
-                o.w = (x.w + y.w) + z.w;
+            unsigned cw[kEmbRows], cp[kEmbRows], ct[kEmbRows];
+#pragma unroll
+            for (int r = 0; r < kEmbRows; ++r) {
+                cw[r] = wr[r][j];
+                cp[r] = pr[r][j];
+                ct[r] = tr[r][j];
             }
-            out[t * H4 + j] = o;
+#pragma unroll
+            for (int r = 0; r < kEmbRows; ++r) {
+                if (t0 + r < T) {
+                    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (ok[r]) {
+                        const float4 x = dequant4(cw[r], r0);
+                        const float4 y = dequant4(cp[r], r1);
+                        const float4 z = dequant4(ct[r], r2);
+                        o.x = (x.x + y.x) + z.x;
+                        o.y = (x.y + y.y) + z.y;
+                        o.z = (x.z + y.z) + z.z;
+                        o.w = (x.w + y.w) + z.w;
+                    }
+                    out[(t0 + r) * H4 + j] = o;
+                }
+            }
         }
     }
 }
@@ -163,7 +184,8 @@ int launch_embedding_sum3(const int8_t* word, int64_t Vw, const int8_t* pos, int
     const bool vec = (H % 4 == 0) && aligned(word, 4) && aligned(pos, 4) && aligned(type, 4) && aligned(out, 16);
     if (vec) {
         const int H4 = (int)(H / 4);
-        const unsigned blocks = (unsigned)(T < 8192 ? T : 8192);  // a token row per workgroup, grid-stride
+        const int64_t groups = (T + kEmbRows - 1) / kEmbRows;
+        const unsigned blocks = (unsigned)(groups < 8192 ? groups : 8192);  // kEmbRows token rows per workgroup trip, grid-stride
         hipLaunchKernelGGL(embedding_sum3_kernel, dim3(blocks), dim3(256), 0, st,
                            reinterpret_cast<const unsigned*>(word), Vw, reinterpret_cast<const unsigned*>(pos), Vp,
                            reinterpret_cast<const unsigned*>(type), Vt, scales, H4, wid, pid, tid, T,
