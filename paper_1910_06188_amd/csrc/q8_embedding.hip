@@ -16,9 +16,10 @@ __device__ __forceinline__ float4 dequant4(unsigned packed, float r)
     return o;
 }
 
-// One workgroup per token row at a time, one thread per 4 codes: the id is wave-uniform (a
-// scalar load), a wave reads 256 contiguous table bytes and writes 1 KiB of contiguous fp32
-// (or 256 B of int8).  Needs H % 4 == 0.
+// A workgroup takes kEmbRows token rows per trip, one thread per 4 codes: the ids are wave-uniform
+// (scalar loads) and fetched first, then the rows; a wave reads 256 contiguous table bytes and writes
+// 1 KiB of contiguous fp32 (or 256 B of int8).  Needs H % 4 == 0.
+constexpr int kEmbRows = 4;
 template <bool kInt8Out>
 __global__ __launch_bounds__(256) void embedding_vec_kernel(const unsigned* __restrict__ table,
                                                              const float* __restrict__ scale, int64_t V, int H4,
@@ -27,17 +28,29 @@ __global__ __launch_bounds__(256) void embedding_vec_kernel(const unsigned* __re
 {
     float r = 0.0f;
     if (!kInt8Out) r = __fdiv_rn(1.0f, scale[0]);
-    for (int64_t t = blockIdx.x; t < T; t += gridDim.x) {
-        const int64_t id = ids[t];
-        const bool ok = id >= 0 && id < V;
-        if (!ok && err_flag && threadIdx.x == 0) err_flag[0] = 1;
-        const unsigned* row = table + (ok ? id : 0) * H4;
+    for (int64_t t0 = (int64_t)blockIdx.x * kEmbRows; t0 < T; t0 += (int64_t)gridDim.x * kEmbRows) {
+        const unsigned* row[kEmbRows];
+        bool ok[kEmbRows];
+#pragma unroll
+        for (int k = 0; k < kEmbRows; ++k) {
+            const int64_t id = ids[min(t0 + k, T - 1)];
+            ok[k] = id >= 0 && id < V;
+            if (!ok[k] && err_flag && threadIdx.x == 0) err_flag[0] = 1;
+            row[k] = table + (ok[k] ? id : 0) * H4;
+        }
         for (int j = threadIdx.x; j < H4; j += 256) {
-            const unsigned packed = ok ? row[j] : 0u;
-            if (kInt8Out)
-                reinterpret_cast<unsigned*>(out)[t * H4 + j] = packed;
-            else
-                reinterpret_cast<float4*>(out)[t * H4 + j] = dequant4(packed, r);
+            unsigned packed[kEmbRows];
+#pragma unroll
+            for (int k = 0; k < kEmbRows; ++k) packed[k] = ok[k] ? row[k][j] : 0u;
+#pragma unroll
+            for (int k = 0; k < kEmbRows; ++k) {
+                if (t0 + k < T) {
+                    if (kInt8Out)
+                        reinterpret_cast<unsigned*>(out)[(t0 + k) * H4 + j] = packed[k];
+                    else
+                        reinterpret_cast<float4*>(out)[(t0 + k) * H4 + j] = dequant4(packed[k], r);
+                }
+            }
         }
     }
 }
@@ -69,7 +82,6 @@ __global__ __launch_bounds__(256) void embedding_scalar_kernel(const int8_t* __r
 // (word + position) + type in fp32.  A workgroup takes kRows token rows per trip: their ids are
 // fetched first, then all their table rows, then the sums are stored -- one row at a time the
 // kernel was bound by the id -> row -> store latency chain, not by bandwidth.  Needs H % 4 == 0.
-constexpr int kEmbRows = 4;
 __global__ __launch_bounds__(256) void embedding_sum3_kernel(const unsigned* __restrict__ word, int64_t Vw,
                                                               const unsigned* __restrict__ pos, int64_t Vp,
                                                               const unsigned* __restrict__ typ, int64_t Vt,
@@ -156,7 +168,8 @@ int launch_embedding(const int8_t* table, const float* scale, int64_t V, int64_t
     const bool vec = (H % 4 == 0) && aligned(table, 4) && aligned(out, out_is_int8 ? 4 : 16);
     if (vec) {
         const int H4 = (int)(H / 4);
-        const unsigned blocks = (unsigned)(T < 8192 ? T : 8192);  // a token row per workgroup, grid-stride
+        const int64_t groups = (T + kEmbRows - 1) / kEmbRows;
+        const unsigned blocks = (unsigned)(groups < 8192 ? groups : 8192);  // kEmbRows token rows per workgroup trip, grid-stride
         const unsigned* tab = reinterpret_cast<const unsigned*>(table);
         if (out_is_int8)
             hipLaunchKernelGGL(embedding_vec_kernel<true>, dim3(blocks), dim3(256), 0, st, tab, scale, V, H4, ids, T,
