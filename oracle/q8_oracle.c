@@ -32,6 +32,7 @@
 #include <math.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #define Q8O_OK 0
 #define Q8O_ERR_NONFINITE 1 /* NaN/Inf input or non-finite scale: outside the method's domain */
@@ -276,6 +277,59 @@ int q8o_layernorm(const float *a, const float *r, const float *gamma, const floa
             float x = pr ? pa[h] + pr[h] : pa[h];
             y[m * H + h] = (float)(((double)x - mean) * rstd * (double)gamma[h] + (double)beta[h]);
         }
+    }
+    return Q8O_OK;
+}
+
+/* Multi-head scaled dot-product attention of one encoder layer, the FP32 operation that sits
+ * between the fused Q|K|V projection and the attention-output FC layer (Section 3: Softmax is
+ * kept in FP32; the two matrix products around it are not FC layers, so they are not quantized
+ * either).  The paper takes the operation from BERT without printing it; this is the standard
+ * definition (Vaswani et al. 2017), written out:
+ *     s[i,j]   = scale * sum_c Q[i,c] K[j,c]  (+ mask[b,j])
+ *     p[i,:]   = softmax over j of s[i,:]
+ *     ctx[i,c] = sum_j p[i,j] V[j,c]
+ * qkv is the projection's output, fp32 [B*S, 3*heads*d]: columns [0, heads*d) hold Q,
+ * the next heads*d hold K, the last heads*d hold V; head h owns columns h*d .. h*d+d-1 of each.
+ * mask (or NULL) is additive, fp32 [B,S], one value per key position (BERT: 0 or -10000).
+ * ctx is fp32 [B*S, heads*d].  Everything is evaluated in binary64 and rounded once. */
+int q8o_attention(const float *qkv, int64_t B, int64_t S, int64_t heads, int64_t d, const float *mask,
+                  double scale, float *ctx, int threads)
+{
+    if (B < 0 || S < 1 || heads < 1 || d < 1) return Q8O_ERR_SHAPE;
+    const int64_t HD = heads * d, ld = 3 * HD;
+    for (int64_t i = 0; i < B * S * ld; ++i)
+        if (!isfinite(qkv[i])) return Q8O_ERR_NONFINITE;
+    if (mask)
+        for (int64_t i = 0; i < B * S; ++i)
+            if (!isfinite(mask[i])) return Q8O_ERR_NONFINITE;
+    if (threads < 1) threads = 1;
+#pragma omp parallel for num_threads(threads) schedule(static)
+    for (int64_t bh = 0; bh < B * heads; ++bh) {
+        const int64_t b = bh / heads, h = bh % heads;
+        double *s = (double *)malloc((size_t)S * sizeof(double));
+        for (int64_t i = 0; i < S; ++i) {
+            const float *q = qkv + (b * S + i) * ld + h * d;
+            double top = -INFINITY;
+            for (int64_t j = 0; j < S; ++j) {
+                const float *k = qkv + (b * S + j) * ld + HD + h * d;
+                double dot = 0.0;
+                for (int64_t c = 0; c < d; ++c) dot += (double)q[c] * (double)k[c];
+                s[j] = scale * dot + (mask ? (double)mask[b * S + j] : 0.0);
+                if (s[j] > top) top = s[j];
+            }
+            double den = 0.0;
+            for (int64_t j = 0; j < S; ++j) {
+                s[j] = exp(s[j] - top);
+                den += s[j];
+            }
+            for (int64_t c = 0; c < d; ++c) {
+                double o = 0.0;
+                for (int64_t j = 0; j < S; ++j) o += s[j] * (double)qkv[(b * S + j) * ld + 2 * HD + h * d + c];
+                ctx[(b * S + i) * HD + h * d + c] = (float)(o / den);
+            }
+        }
+        free(s);
     }
     return Q8O_OK;
 }

@@ -195,6 +195,20 @@ def layernorm(a, gamma, beta, eps=1e-12, residual=None) -> np.ndarray:
                                _p(y, C.c_float)), "layernorm")
     return y
 
+def attention(qkv, B: int, S: int, heads: int, d: int, mask=None, scale=None, threads: int = 1) -> np.ndarray:
+    """softmax(scale * Q K^T + mask) V per head on the fused projection output qkv [B*S, 3*heads*d]; fp64 inside."""
+    qkv = _f32(qkv)
+    assert qkv.shape == (B * S, 3 * heads * d)
+    mk = _f32(mask).reshape(B, S) if mask is not None else None
+    if scale is None:
+        scale = 1.0 / np.sqrt(float(d))
+    ctx = np.empty((B * S, heads * d), dtype=np.float32)
+    _check(lib().q8o_attention(_p(qkv, C.c_float), C.c_int64(B), C.c_int64(S), C.c_int64(heads), C.c_int64(d),
+                               _p(mk, C.c_float) if mk is not None else None, C.c_double(float(scale)),
+                               _p(ctx, C.c_float), C.c_int(threads)), "attention")
+    return ctx
+
+
 def quantize_tensor(x):
     """Dynamic per-tensor quantization: S = 127 / max|x| (Eq. 3), then Eq. 1."""
     s = scale(absmax(x))

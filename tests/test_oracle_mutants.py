@@ -48,6 +48,13 @@ MUTANTS = [
     ("layernorm_unbiased_variance", "double rstd = 1.0 / sqrt(ss / (double)H + eps);", "double rstd = 1.0 / sqrt(ss / (double)(H - 1) + eps);"),
     ("layernorm_no_mean", "double mean = sum / (double)H, ss = 0.0;", "double mean = 0.0 * sum, ss = 0.0;"),
     ("layernorm_drops_residual", "float x = pr ? pa[h] + pr[h] : pa[h];\n            y[m * H + h]", "float x = pa[h];\n            y[m * H + h]"),
+    ("attention_no_scale", "s[j] = scale * dot + (mask", "s[j] = dot + (mask"),
+    ("attention_keys_are_queries", "const float *k = qkv + (b * S + j) * ld + HD + h * d;", "const float *k = qkv + (b * S + j) * ld + h * d;"),
+    ("attention_values_are_keys", "o += s[j] * (double)qkv[(b * S + j) * ld + 2 * HD + h * d + c];", "o += s[j] * (double)qkv[(b * S + j) * ld + HD + h * d + c];"),
+    ("attention_mask_by_query", "(double)mask[b * S + j] : 0.0);", "(double)mask[b * S + i] : 0.0);"),
+    ("attention_not_normalised", "(float)(o / den);", "(float)(o);"),
+    ("attention_head_offset_dropped", "const float *q = qkv + (b * S + i) * ld + h * d;", "const float *q = qkv + (b * S + i) * ld;"),
+    ("attention_mask_of_sequence_0", "(double)mask[b * S + j] : 0.0);", "(double)mask[j] : 0.0);"),
     ("layernorm_beta_scaled", "* (double)gamma[h] + (double)beta[h]);", "* (double)gamma[h] + (double)beta[h] * (double)gamma[h]);"),
 ]
 

@@ -399,3 +399,108 @@ def test_layernorm_invariants():
     np.testing.assert_array_equal(y_perm[::-1], O.layernorm(x, one, zero, eps=0.0))
     with pytest.raises(O.OracleError):
         O.layernorm(np.array([[np.inf, 1.0]], np.float32), np.ones(2, np.float32), np.zeros(2, np.float32))
+
+
+# ---------------------------------------------------------------- FP32 glue: softmax attention (Section 3)
+def _attention_library(qkv, B, S, heads, d, mask, scale):
+    """The same operation from library routines in float64: scipy's softmax and NumPy's matmul."""
+    from scipy.special import softmax
+    x = qkv.astype(np.float64).reshape(B, S, 3, heads, d)
+    q, k, v = (x[:, :, i].transpose(0, 2, 1, 3) for i in range(3))          # [B, heads, S, d]
+    s = scale * (q @ k.transpose(0, 1, 3, 2))
+    if mask is not None:
+        s = s + mask.astype(np.float64).reshape(B, 1, 1, S)
+    return (softmax(s, axis=-1) @ v).transpose(0, 2, 1, 3).reshape(B * S, heads * d)
+
+
+def test_attention_hand_cases():
+    # one head of width 1, two tokens, scale 1: q = [1, 0], k = [0, ln 3], v = [4, 8]
+    #   token 0: scores [0, ln 3] -> weights [1/4, 3/4] -> 1 + 6 = 7;  token 1: scores [0, 0] -> mean(v) = 6
+    qkv = np.array([[1.0, 0.0, 4.0], [0.0, np.log(3.0), 8.0]], dtype=np.float32)
+    out = O.attention(qkv, 1, 2, 1, 1, scale=1.0)
+    np.testing.assert_allclose(out[:, 0], [7.0, 6.0], rtol=2e-7)
+    # the scale multiplies the scores: with scale 2 the weights of token 0 are [1/10, 9/10] -> 0.4 + 7.2
+    np.testing.assert_allclose(O.attention(qkv, 1, 2, 1, 1, scale=2.0)[0, 0], 7.6, rtol=2e-7)
+    # default scale is 1/sqrt(d): d = 4, q = (2,0,0,0), k0 = 0, k1 = (ln 3, 0,0,0) -> score 2 ln3 / 2 = ln 3 again
+    row0 = [2, 0, 0, 0] + [0, 0, 0, 0] + [4, 1, 0, -4]
+    row1 = [0, 0, 0, 0] + [np.log(3.0), 0, 0, 0] + [8, 1, 4, 4]
+    out = O.attention(np.array([row0, row1], dtype=np.float32), 1, 2, 1, 4)
+    np.testing.assert_allclose(out[0], [7.0, 1.0, 3.0, 2.0], rtol=2e-7)
+    np.testing.assert_allclose(out[1], [6.0, 1.0, 2.0, 0.0], rtol=2e-7, atol=1e-30)
+    # an additive mask of -10000 on key 1 removes it: both tokens return v of key 0
+    out = O.attention(qkv, 1, 2, 1, 1, mask=np.array([[0.0, -10000.0]], np.float32), scale=1.0)
+    np.testing.assert_array_equal(out[:, 0], [4.0, 4.0])
+
+
+def test_attention_closed_forms():
+    g = synth.rng(301)
+    B, S, heads, d = 2, 9, 3, 8
+    qkv = synth.activations(g, B * S, 3 * heads * d)
+    # all queries zero -> uniform weights -> every token gets the mean of its sequence's V rows, head by head
+    z = qkv.copy()
+    z[:, :heads * d] = 0
+    got = O.attention(z, B, S, heads, d).astype(np.float64)
+    v = z[:, 2 * heads * d:].astype(np.float64).reshape(B, S, heads * d)
+    np.testing.assert_allclose(got.reshape(B, S, -1), np.repeat(v.mean(axis=1, keepdims=True), S, axis=1), rtol=1e-6, atol=1e-7)
+    # ... and with keys 0..3 masked out, the mean over the remaining keys
+    mask = np.zeros((B, S), np.float32)
+    mask[:, :4] = -10000.0
+    got = O.attention(z, B, S, heads, d, mask=mask).astype(np.float64)
+    np.testing.assert_allclose(got.reshape(B, S, -1), np.repeat(v[:, 4:].mean(axis=1, keepdims=True), S, axis=1), rtol=1e-6, atol=1e-7)
+    # one key far ahead of the others: query i = 50 e_0, key (S-1-i) = e_0 * 50, all other keys 0 -> output = V[S-1-i]
+    one = np.zeros((S, 3 * d), np.float32)
+    one[:, 0] = 50.0
+    one[:, 2 * d:] = synth.activations(g, S, d)
+    krows = np.zeros((S, d), np.float32)
+    krows[:, 0] = 0.0
+    one[:, d:2 * d] = krows
+    for i in range(S):
+        kk = one.copy()
+        kk[S - 1 - i, d] = 50.0
+        out = O.attention(kk, 1, S, 1, d, scale=1.0)
+        np.testing.assert_allclose(out[i], kk[S - 1 - i, 2 * d:], rtol=1e-6, atol=1e-7)
+
+
+def test_attention_matches_library_routines():
+    g = synth.rng(302)
+    for (B, S, heads, d, use_mask, scale) in [(2, 7, 3, 5, True, None), (1, 40, 2, 64, False, None), (3, 17, 4, 16, True, 0.37)]:
+        qkv = synth.activations(g, B * S, 3 * heads * d)
+        mask = np.where(g.random((B, S)) < 0.3, -10000.0, 0.0).astype(np.float32) if use_mask else None
+        if mask is not None:
+            mask[:, 0] = 0.0
+        sc = 1.0 / np.sqrt(d) if scale is None else scale
+        ref = _attention_library(qkv, B, S, heads, d, mask, sc)
+        got = O.attention(qkv, B, S, heads, d, mask=mask, scale=scale).astype(np.float64)
+        assert np.abs(got - ref).max() <= 1.01 * np.spacing(np.float32(np.abs(ref).max())) / 2 + 1e-12
+
+
+def test_attention_invariants():
+    g = synth.rng(303)
+    B, S, heads, d = 2, 12, 2, 8
+    HD = heads * d
+    qkv = synth.activations(g, B * S, 3 * HD)
+    mask = (np.round(g.standard_normal((B, S)) * 8) / 4).astype(np.float32)   # multiples of 1/4: mask + 3 is exact
+    base = O.attention(qkv, B, S, heads, d, mask=mask)
+    # every output is a convex combination of its sequence's V rows
+    v = qkv[:, 2 * HD:].reshape(B, S, HD)
+    out = base.reshape(B, S, HD)
+    assert (out <= v.max(axis=1, keepdims=True) + 1e-6).all() and (out >= v.min(axis=1, keepdims=True) - 1e-6).all()
+    # softmax is shift invariant: a constant added to one sequence's mask changes nothing
+    np.testing.assert_allclose(O.attention(qkv, B, S, heads, d, mask=mask + np.float32(3.0)), base, rtol=1e-6, atol=1e-7)
+    # permuting the key/value rows of a sequence (with their mask entries) leaves every output in place
+    perm = g.permutation(S)
+    x = qkv.reshape(B, S, 3 * HD).copy()
+    x[:, :, HD:] = x[:, perm, HD:]
+    got = O.attention(x.reshape(B * S, 3 * HD), B, S, heads, d, mask=mask[:, perm])
+    np.testing.assert_allclose(got, base, rtol=1e-6, atol=1e-7)
+    # heads and sequences are independent: new keys for head 1 of sequence 1 move only that block
+    y = qkv.copy()
+    y[S:, HD + d:HD + 2 * d] += np.float32(1.0) * synth.activations(g, S, d)
+    got = O.attention(y, B, S, heads, d, mask=mask)
+    np.testing.assert_array_equal(got[:S], base[:S])
+    np.testing.assert_array_equal(got[S:, :d], base[S:, :d])
+    assert np.abs(got[S:, d:] - base[S:, d:]).max() > 1e-3
+    with pytest.raises(O.OracleError):
+        bad = qkv.copy()
+        bad[3, 5] = np.nan
+        O.attention(bad, B, S, heads, d)
