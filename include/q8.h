@@ -245,6 +245,35 @@ q8_status q8_embedding_sum3_layernorm(const int8_t* word, int64_t Vw, const int8
                                       float* y, float* amax_slots, const float* q_scale, int8_t* q_out,
                                       int32_t* err_flag, void* stream);
 
+/*
+ * Multi-head softmax attention in FP32 (Section 3: Softmax is kept in FP32, and only Embedding
+ * and FC layers are quantized, so the two matrix products around it stay FP32 too) -- the
+ * operation between the fused Q|K|V FC layer and the attention-output FC layer -- with the
+ * first half of that next layer's quantizer behind it, as in q8_layernorm_absmax:
+ *     s[i,j]   = scale * sum_c Q[i,c] K[j,c]  (+ mask[b,j])        i, j tokens of sequence b
+ *     p[i,:]   = softmax over j of s[i,:]
+ *     ctx[i,c] = sum_j p[i,j] V[j,c]
+ *   qkv fp32[B*S, 3*heads*d]: the output of q8_linear(_f32) with n_groups = 3 -- columns
+ *   [0, heads*d) hold Q, the next heads*d hold K, the last heads*d hold V; head h owns columns
+ *   h*d .. h*d+d-1 of each.  B sequences of S tokens, rows in sequence order.
+ *   mask fp32[B,S] or NULL: added to the scores of key j (BERT: 0, or -10000 for padding).
+ *   scale host float > 0 (BERT: 1/sqrt(d)).
+ *   ctx fp32[B*S, heads*d], or NULL when only the codes are wanted.
+ *   amax_slots fp32[Q8_AMAX_SLOTS] or NULL: partial maxima of |ctx| for q8_quantize_amax.
+ *   q_scale fp32[1] and q_out int8[B*S, heads*d], both or neither: q_out = Quantize(ctx | q_scale[0], 127)
+ *   (Eq. 1 on the fp32 value), the whole quantizer of the next FC layer under a stored scale (Eq. 4).
+ * Arithmetic is binary32 throughout (fp32 matrix pipes, running-maximum softmax, exp2): ctx agrees
+ * with the exact result to about 1e-6 of the largest |V| of its head as long as the scores stay
+ * within a few tens; a sequence whose every key carries a large negative mask loses the low bits of
+ * its scores to that offset.  Inputs must be finite.
+ * B >= 0 (B = 0: nothing written, slots cleared); S >= 1; heads, d >= 1.  d = 64 with 16-byte
+ * aligned qkv and ctx (4-byte q_out) takes the MFMA kernel; other widths or alignments take a
+ * slower kernel that needs S <= 16384 (Q8_ERR_SHAPE beyond).
+ */
+q8_status q8_attention(const float* qkv, int64_t B, int64_t S, int heads, int d,
+                       const float* mask, float scale, float* ctx, float* amax_slots,
+                       const float* q_scale, int8_t* q_out, void* stream);
+
 /* Library version string and a short text for a status code (host pointers, static storage). */
 const char* q8_version(void);
 const char* q8_status_str(q8_status s);

@@ -236,6 +236,23 @@ q8_status q8_embedding_sum3_layernorm(const int8_t* word, int64_t Vw, const int8
                : Q8_OK;
 }
 
+q8_status q8_attention(const float* qkv, int64_t B, int64_t S, int heads, int d, const float* mask, float scale, float* ctx,
+                       float* amax_slots, const float* q_scale, int8_t* q_out, void* stream)
+{
+    if (B < 0 || S < 1 || heads < 1 || d < 1 || !(scale > 0.0f) || !(scale < 3.0e38f)) return Q8_ERR_SHAPE;
+    if ((int64_t)heads * d > ((int64_t)1 << 24) || B > ((int64_t)1 << 40) / S) return Q8_ERR_SHAPE;
+    if ((q_scale == nullptr) != (q_out == nullptr)) return Q8_ERR_NULL;
+    if (B > 0 && (!qkv || (!ctx && !q_out))) return Q8_ERR_NULL;
+    if (misaligned(qkv, 4) || misaligned(mask, 4) || misaligned(ctx, 4) || misaligned(amax_slots, 4) || misaligned(q_scale, 4))
+        return Q8_ERR_ALIGN;
+    if (B > 0 && !q8::attention_mfma_eligible(qkv, B, S, heads, d, ctx, q_out)) {
+        if (S > q8::attention_generic_max_s() || B * heads * S >= ((int64_t)1 << 31)) return Q8_ERR_SHAPE;
+    }
+    return q8::launch_attention(qkv, B, S, heads, d, mask, scale, ctx, amax_slots, q_scale, q_out, as_stream(stream))
+               ? Q8_ERR_LAUNCH
+               : Q8_OK;
+}
+
 const char* q8_version(void) { return "q8 0.1.0 (gfx950)"; }
 
 const char* q8_status_str(q8_status s)

@@ -1,0 +1,365 @@
+// FP32 multi-head softmax attention, the operation between the fused Q|K|V FC layer and the
+// attention-output FC layer of an encoder layer.  Section 3 keeps Softmax in FP32 and quantizes
+// only Embedding and FC layers, so both matrix products around the softmax stay FP32 as well:
+//     s[i,j] = scale * <Q[i,:], K[j,:]> (+ mask[j]),   p = softmax_j(s),   ctx[i,:] = sum_j p[i,j] V[j,:]
+// Behind it sits the first half of the next FC layer's quantizer (Section 4.1): the abs-max of
+// ctx goes to per-workgroup slots, or, with a stored scale (Eq. 4), the int8 codes of ctx are
+// written directly (Eq. 1) and ctx itself need not be stored at all.
+//
+// MFMA kernel (head width 64): a workgroup of four waves owns 128 queries of one (sequence,
+// head); each wave keeps its 32 query rows in registers (pre-multiplied by scale * log2 e) and
+// walks the keys in stages of 64, K and V tiles staged in LDS and shared by the four waves.
+// Scores are formed transposed, S^T = K Q^T, with v_mfma_f32_32x32x2_f32: a lane then holds 16
+// keys of ONE query per 32-key block, so the softmax statistics are per-lane loops plus a single
+// exchange between the two half-waves, and the probabilities sit exactly where the B operand of
+// O^T += V^T P^T wants them -- no data movement between the two products.  Softmax is the
+// running-maximum form (scores never exist in memory), evaluated with exp2.
+// Work per (sequence, head): 4 S^2 64 flops; bound by the fp32 matrix pipes (157 TFLOP/s), the
+// traffic (qkv read once per query block from L2, ctx written once) is small beside it.
+#include "q8_device.h"
+#include "q8_launch.h"
+
+namespace q8 {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int kAtD = 64;                   // head width of the MFMA kernel
+constexpr int kAtWaves = 4;                // waves per workgroup
+constexpr int kAtThreads = kAtWaves * 64;
+constexpr int kAtQW = 32;                  // queries per wave
+constexpr int kAtQB = kAtQW * kAtWaves;    // queries per workgroup
+constexpr int kAtKB = 64;                  // keys per stage
+// LDS row strides in floats.  K rows are read 16 bytes per lane, 16 lanes (keys) per cycle: 68 = 4 (mod 64)
+// spreads them over all 64 banks.  V rows are read 4 bytes per lane, the two half-waves four keys apart:
+// 4 * 72 = 32 (mod 64) puts the halves on disjoint banks.
+constexpr int kAtKStride = 68;
+constexpr int kAtVStride = 72;
+constexpr int kAtStageFloats = kAtKB * kAtKStride + kAtKB * kAtVStride + kAtKB;  // K tile, V tile, mask row
+constexpr int kAtSlots = 2048;             // abs-max slots (= Q8_AMAX_SLOTS)
+
+struct AttnArgs {
+    const float* qkv;     // [B*S, 3*heads*d]
+    const float* mask;    // [B, S] additive, or null
+    float* ctx;           // [B*S, heads*d] or null
+    unsigned* slots;      // abs-max slots or null
+    const float* q_scale; // stored scale of the next FC or null
+    unsigned* q_out;      // int8 codes of ctx, packed four to a dword, or null
+    int64_t S;
+    int heads;
+    int n_qblocks;        // ceil(S / 128)
+    int slots_atomic;     // more workgroups than slots: fold with atomics into cleared slots
+    float c;              // scale * log2(e)
+};
+
+__global__ __launch_bounds__(kAtThreads, 2) void attention_mfma_kernel(AttnArgs a)
+{
+    extern __shared__ __align__(16) float lds[];
+    __shared__ unsigned wave_amax[kAtWaves];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lq = lane & 31, hi = lane >> 5;
+    // Workgroups of one (sequence, head) are neighbours in the logical order; each XCD takes a contiguous
+    // run of it so that they find the K and V rows in the same L2.
+    int wid = blockIdx.x;
+    const int total = gridDim.x;
+    if ((total & 7) == 0) wid = (wid & 7) * (total >> 3) + (wid >> 3);
+    const int qb = wid % a.n_qblocks;
+    const int bh = wid / a.n_qblocks;
+    const int h = bh % a.heads;
+    const int64_t b = bh / a.heads;
+    const int64_t S = a.S, HD = (int64_t)a.heads * kAtD, ld = 3 * HD;
+    const float* base = a.qkv + b * S * ld + (int64_t)h * kAtD;   // Q of token 0 of this sequence and head
+    const int64_t q0 = (int64_t)qb * kAtQB + wave * kAtQW;
+
+    // The wave's queries: lane (lq, hi) holds, for t = 0..7, columns 8t + 4hi .. 8t + 4hi + 3 of query lq.
+    // A row beyond the sequence repeats the last one (computed, never stored).
+    float q[32];
+    {
+        const int64_t qrow = (q0 + lq < S) ? q0 + lq : S - 1;
+        const float4* qp = reinterpret_cast<const float4*>(base + qrow * ld) + hi;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const float4 v = qp[2 * t];
+            q[4 * t + 0] = v.x * a.c;
+            q[4 * t + 1] = v.y * a.c;
+            q[4 * t + 2] = v.z * a.c;
+            q[4 * t + 3] = v.w * a.c;
+        }
+    }
+
+    // Staging: thread t carries chunks t, t + 256, ... of the 64 x 16 float4 chunks of a K and of a V tile.
+    float4 k0r, k1r, k2r, k3r, v0r, v1r, v2r, v3r;
+    float mreg = 0.0f;
+    const int n_stages = (int)((S + kAtKB - 1) / kAtKB);
+    const int st_key = tid >> 4, st_ch = tid & 15;   // chunk i of this thread: key st_key + 16 i, 16-byte column st_ch
+#define Q8_AT_FETCH1(i, kr, vr)                                                              \
+    {                                                                                        \
+        const int64_t row = (k0 + st_key + 16 * (i) < S) ? k0 + st_key + 16 * (i) : S - 1;   \
+        const float4* p = reinterpret_cast<const float4*>(base + row * ld + HD) + st_ch;     \
+        kr = p[0];                                                                           \
+        vr = p[HD / 4];                                                                      \
+    }
+#define Q8_AT_FETCH(stage)                                                                   \
+    {                                                                                        \
+        const int64_t k0 = (int64_t)(stage) * kAtKB;                                         \
+        Q8_AT_FETCH1(0, k0r, v0r) Q8_AT_FETCH1(1, k1r, v1r) Q8_AT_FETCH1(2, k2r, v2r) Q8_AT_FETCH1(3, k3r, v3r) \
+        if (tid < kAtKB) {                                                                   \
+            const int64_t key = k0 + tid;                                                    \
+            /* beyond the sequence: -inf, the key gets weight 0 whatever its (repeated) row holds */ \
+            mreg = (key < S) ? (a.mask ? a.mask[b * S + key] * 1.44269504088896341f : 0.0f) : -__builtin_inff(); \
+        }                                                                                    \
+    }
+#define Q8_AT_STASH1(i, kr, vr)                                                              \
+    *reinterpret_cast<float4*>(Ks_w + (st_key + 16 * (i)) * kAtKStride + 4 * st_ch) = kr;    \
+    *reinterpret_cast<float4*>(Vs_w + (st_key + 16 * (i)) * kAtVStride + 4 * st_ch) = vr;
+#define Q8_AT_STASH(buf)                                                                     \
+    {                                                                                        \
+        float* Ks_w = lds + (buf) * kAtStageFloats;                                          \
+        float* Vs_w = Ks_w + kAtKB * kAtKStride;                                             \
+        Q8_AT_STASH1(0, k0r, v0r) Q8_AT_STASH1(1, k1r, v1r) Q8_AT_STASH1(2, k2r, v2r) Q8_AT_STASH1(3, k3r, v3r) \
+        if (tid < kAtKB) Vs_w[kAtKB * kAtVStride + tid] = mreg;                              \
+    }
+
+    v16f o[2];           // O^T: o[blk][e] = ctx[query lq][column 32 blk + 8 (e/4) + 4 hi + e%4], not yet normalised
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o[0][e] = o[1][e] = 0.0f;
+    float m_run = -__builtin_inff();   // running maximum of this lane's query (log2 units), same in both half-waves
+    float l_run = 0.0f;                // this lane's share of the running denominator
+
+    Q8_AT_FETCH(0)
+    Q8_AT_STASH(0)
+    __syncthreads();
+
+    for (int st = 0; st < n_stages; ++st) {
+        const bool more = st + 1 < n_stages;
+        if (more) Q8_AT_FETCH(st + 1)
+        const float* Ks = lds + (st & 1) * kAtStageFloats;
+        const float* Vs = Ks + kAtKB * kAtKStride;
+        const float* Ms = Vs + kAtKB * kAtVStride;
+
+        // S^T = K Q^T for the two 32-key blocks of the stage.  MFMA number 4t + i pairs column 8t + i
+        // (lower half-wave) with column 8t + 4 + i (upper half-wave) of both operands.
+        v16f s[2];
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s[sub][e] = 0.0f;
+            const float* krow = Ks + (sub * 32 + lq) * kAtKStride + 4 * hi;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const float4 kf = *reinterpret_cast<const float4*>(krow + 8 * t);
+                s[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.x, q[4 * t + 0], s[sub], 0, 0, 0);
+                s[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.y, q[4 * t + 1], s[sub], 0, 0, 0);
+                s[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.z, q[4 * t + 2], s[sub], 0, 0, 0);
+                s[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.w, q[4 * t + 3], s[sub], 0, 0, 0);
+            }
+        }
+        // s[sub][e] of lane (lq, hi) is the score of query lq against key 32 sub + 8 (e/4) + 4 hi + e%4.
+        float mx = -__builtin_inff();
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float4 mk = *reinterpret_cast<const float4*>(Ms + sub * 32 + 8 * g + 4 * hi);
+                s[sub][4 * g + 0] += mk.x;
+                s[sub][4 * g + 1] += mk.y;
+                s[sub][4 * g + 2] += mk.z;
+                s[sub][4 * g + 3] += mk.w;
+                mx = __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fmaxf(s[sub][4 * g], s[sub][4 * g + 1]),
+                                                         __builtin_fmaxf(s[sub][4 * g + 2], s[sub][4 * g + 3])));
+            }
+        mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
+        // Key 0 of stage 0 is always inside the sequence, so the maximum is finite from the first stage on.
+        const float m_new = __builtin_fmaxf(m_run, mx);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        float psum = 0.0f;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                s[sub][e] = __builtin_amdgcn_exp2f(s[sub][e] - m_new);
+                psum += s[sub][e];
+            }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            o[0][e] *= alpha;
+            o[1][e] *= alpha;
+        }
+        // O^T += V^T P^T: MFMA (sub, e) pairs key 32 sub + 8 (e/4) + e%4 (lower half-wave) with the key four
+        // further on (upper half-wave) -- the keys whose probabilities the two halves hold in register e.
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const float* vrow = Vs + (sub * 32 + 8 * (e >> 2) + 4 * hi + (e & 3)) * kAtVStride + lq;
+                o[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[0], s[sub][e], o[0], 0, 0, 0);
+                o[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[32], s[sub][e], o[1], 0, 0, 0);
+            }
+        if (more) Q8_AT_STASH((st + 1) & 1)
+        __syncthreads();
+    }
+
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const float inv = 1.0f / l_tot;
+    const bool live = q0 + lq < S;
+    const float qs = a.q_out ? a.q_scale[0] : 0.0f;
+    float amax = 0.0f;
+    const int64_t out_off = (b * S + q0 + lq) * HD + (int64_t)h * kAtD + 4 * hi;
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            float4 v;
+            v.x = o[blk][4 * g + 0] * inv;
+            v.y = o[blk][4 * g + 1] * inv;
+            v.z = o[blk][4 * g + 2] * inv;
+            v.w = o[blk][4 * g + 3] * inv;
+            if (live) {
+                const int64_t off = out_off + 32 * blk + 8 * g;
+                if (a.ctx) *reinterpret_cast<float4*>(a.ctx + off) = v;
+                if (a.q_out)  // Eq. 1 with the stored scale of the next FC layer, four codes per lane
+                    a.q_out[off >> 2] = ((unsigned)quantize_code(v.x, qs) & 0xffu) | (((unsigned)quantize_code(v.y, qs) & 0xffu) << 8) |
+                                        (((unsigned)quantize_code(v.z, qs) & 0xffu) << 16) | ((unsigned)quantize_code(v.w, qs) << 24);
+                amax = __builtin_fmaxf(amax, __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(v.x), __builtin_fabsf(v.y)),
+                                                            __builtin_fmaxf(__builtin_fabsf(v.z), __builtin_fabsf(v.w))));
+            }
+        }
+    if (a.slots) {
+        unsigned m = wave_max_u32(__float_as_uint(amax));  // non-negative floats order like their bit patterns
+        if (lane == 0) wave_amax[wave] = m;
+        __syncthreads();
+        if (tid == 0) {
+#pragma unroll
+            for (int w = 1; w < kAtWaves; ++w) m = max(m, wave_amax[w]);
+            if (a.slots_atomic) {
+                if (m) atomicMax(a.slots + (blockIdx.x % kAtSlots), m);
+            } else {
+                a.slots[blockIdx.x] = m;
+            }
+        }
+        if (!a.slots_atomic && blockIdx.x == 0)  // slots no workgroup owns
+            for (int i = gridDim.x + tid; i < kAtSlots; i += kAtThreads) a.slots[i] = 0u;
+    }
+}
+
+// Any head width and alignment: one wave per (sequence, head, query).  Scores go to LDS, the softmax is the
+// plain three-step form, then each lane sums its columns of V.  Slow; same tolerance.
+__global__ __launch_bounds__(64) void attention_generic_kernel(const float* __restrict__ qkv, const float* __restrict__ mask,
+                                                               float* __restrict__ ctx, unsigned* __restrict__ slots,
+                                                               const float* __restrict__ q_scale, int8_t* __restrict__ q_out,
+                                                               int64_t S, int heads, int d, float c)
+{
+    extern __shared__ __align__(16) float p[];   // S scores / probabilities
+    const int lane = threadIdx.x;
+    const int64_t i = blockIdx.x % S;
+    const int64_t bh = blockIdx.x / S;
+    const int h = (int)(bh % heads);
+    const int64_t b = bh / heads;
+    const int64_t HD = (int64_t)heads * d, ld = 3 * HD;
+    const float* qrow = qkv + (b * S + i) * ld + (int64_t)h * d;
+    float mx = -__builtin_inff();
+    for (int64_t j = lane; j < S; j += 64) {
+        const float* krow = qkv + (b * S + j) * ld + HD + (int64_t)h * d;
+        float dot = 0.0f;
+        for (int k = 0; k < d; ++k) dot = __builtin_fmaf(qrow[k] * c, krow[k], dot);
+        if (mask) dot += mask[b * S + j] * 1.44269504088896341f;
+        p[j] = dot;
+        mx = __builtin_fmaxf(mx, dot);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx = __builtin_fmaxf(mx, __shfl_xor(mx, off, 64));
+    float den = 0.0f;
+    for (int64_t j = lane; j < S; j += 64) {
+        const float e = __builtin_amdgcn_exp2f(p[j] - mx);
+        p[j] = e;
+        den += e;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) den += __shfl_xor(den, off, 64);
+    __syncthreads();
+    const float inv = 1.0f / den;
+    const float qs = q_out ? q_scale[0] : 0.0f;
+    float amax = 0.0f;
+    for (int k = lane; k < d; k += 64) {
+        const float* vcol = qkv + b * S * ld + 2 * HD + (int64_t)h * d + k;
+        float acc = 0.0f;
+        for (int64_t j = 0; j < S; ++j) acc = __builtin_fmaf(p[j], vcol[j * ld], acc);
+        const float v = acc * inv;
+        const int64_t off = (b * S + i) * HD + (int64_t)h * d + k;
+        if (ctx) ctx[off] = v;
+        if (q_out) q_out[off] = (int8_t)quantize_code(v, qs);
+        amax = __builtin_fmaxf(amax, __builtin_fabsf(v));
+    }
+    if (slots) {
+        const unsigned m = wave_max_u32(__float_as_uint(amax));
+        if (lane == 0 && m) atomicMax(slots + (blockIdx.x % kAtSlots), m);
+    }
+}
+
+#undef Q8_AT_FETCH1
+#undef Q8_AT_FETCH
+#undef Q8_AT_STASH1
+#undef Q8_AT_STASH
+
+__global__ void attention_slots_clear_kernel(unsigned* slots)
+{
+    for (int i = threadIdx.x; i < kAtSlots; i += 256) slots[i] = 0u;
+}
+
+static bool at_aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int attention_generic_max_s() { return 16384; }   // scores of one query in 64 KiB of LDS
+
+bool attention_mfma_eligible(const float* qkv, int64_t B, int64_t S, int heads, int d, const float* ctx, const int8_t* q_out)
+{
+    const int64_t wgs = B * heads * ((S + kAtQB - 1) / kAtQB);
+    return d == kAtD && at_aligned(qkv, 16) && (!ctx || at_aligned(ctx, 16)) && at_aligned(q_out, 4) &&
+           wgs < ((int64_t)1 << 31);
+}
+
+int launch_attention(const float* qkv, int64_t B, int64_t S, int heads, int d, const float* mask, float scale, float* ctx,
+                     float* amax_slots, const float* q_scale, int8_t* q_out, hipStream_t st)
+{
+    unsigned* slots = reinterpret_cast<unsigned*>(amax_slots);
+    if (B == 0) {
+        if (slots) hipLaunchKernelGGL(attention_slots_clear_kernel, dim3(1), dim3(256), 0, st, slots);
+        return hipGetLastError() == hipSuccess ? 0 : 1;
+    }
+    const float c = scale * 1.44269504088896341f;
+    const int64_t n_qblocks = (S + kAtQB - 1) / kAtQB;
+    const int64_t wgs = B * heads * n_qblocks;
+    if (attention_mfma_eligible(qkv, B, S, heads, d, ctx, q_out)) {
+        AttnArgs a;
+        a.qkv = qkv;
+        a.mask = mask;
+        a.ctx = ctx;
+        a.slots = slots;
+        a.q_scale = q_scale;
+        a.q_out = reinterpret_cast<unsigned*>(q_out);
+        a.S = S;
+        a.heads = heads;
+        a.n_qblocks = (int)n_qblocks;
+        a.slots_atomic = wgs > kAtSlots;
+        a.c = c;
+        if (slots && a.slots_atomic) hipLaunchKernelGGL(attention_slots_clear_kernel, dim3(1), dim3(256), 0, st, slots);
+        static bool attr_set = false;   // more than 64 KiB of dynamic LDS has to be asked for once
+        const size_t lds_bytes = 2 * kAtStageFloats * sizeof(float);
+        if (!attr_set) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(attention_mfma_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+                return 1;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(attention_mfma_kernel, dim3((unsigned)wgs), dim3(kAtThreads), lds_bytes, st, a);
+    } else {
+        const int64_t blocks = B * heads * S;
+        if (blocks >= ((int64_t)1 << 31)) return 1;
+        if (slots) hipLaunchKernelGGL(attention_slots_clear_kernel, dim3(1), dim3(256), 0, st, slots);
+        hipLaunchKernelGGL(attention_generic_kernel, dim3((unsigned)blocks), dim3(64), (size_t)S * sizeof(float), st, qkv,
+                           mask, ctx, slots, q_scale, q_out, S, heads, d, c);
+    }
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+}  // namespace q8

@@ -60,6 +60,15 @@ int launch_embedding_sum3_layernorm(const int8_t* word, int64_t Vw, const int8_t
                                     const float* beta, float eps, float* y, float* amax_slots, const float* q_scale,
                                     int8_t* q_out, int32_t* err_flag, hipStream_t st);
 
+// FP32 softmax attention on the fused Q|K|V projection output (Section 3 keeps Softmax in FP32), with the
+// abs-max slots or the stored-scale int8 codes of its result for the attention-output FC layer behind it.
+// attention_mfma_eligible: head width 64 and 16-byte aligned tensors take the MFMA kernel, anything else a
+// generic one that keeps one query's scores in LDS (S <= attention_generic_max_s()).
+bool attention_mfma_eligible(const float* qkv, int64_t B, int64_t S, int heads, int d, const float* ctx, const int8_t* q_out);
+int attention_generic_max_s();
+int launch_attention(const float* qkv, int64_t B, int64_t S, int heads, int d, const float* mask, float scale, float* ctx,
+                     float* amax_slots, const float* q_scale, int8_t* q_out, hipStream_t st);
+
 // Tuning hook used by the benchmark and tests: selects the MFMA tile variant
 // (0 = automatic choice from the shape).
 void set_gemm_variant(int v);

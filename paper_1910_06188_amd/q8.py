@@ -46,7 +46,8 @@ _lib.q8_ste_backward.argtypes = [_vp, _i64, _vp, _vp]
 _lib.q8_layernorm_absmax.argtypes = [_vp, _vp, _vp, _vp, _f32, _i64, _i64, _vp, _vp, _vp, _vp, _vp]
 _lib.q8_embedding_sum3_layernorm.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _f32,
                                              _vp, _vp, _vp, _vp, _vp, _vp]
-for _f in ("q8_layernorm_absmax", "q8_embedding_sum3_layernorm", "q8_fake_quantize", "q8_ema_update", "q8_fake_quantize_ema", "q8_ste_backward", "q8_absmax", "q8_scale_from_amax", "q8_quantize", "q8_quantize_amax", "q8_linear", "q8_linear_f32", "q8_embedding",
+_lib.q8_attention.argtypes = [_vp, _i64, _i64, _i32, _i32, _vp, _f32, _vp, _vp, _vp, _vp, _vp]
+for _f in ("q8_attention", "q8_layernorm_absmax", "q8_embedding_sum3_layernorm", "q8_fake_quantize", "q8_ema_update", "q8_fake_quantize_ema", "q8_ste_backward", "q8_absmax", "q8_scale_from_amax", "q8_quantize", "q8_quantize_amax", "q8_linear", "q8_linear_f32", "q8_embedding",
            "q8_embedding_sum3"):
     getattr(_lib, _f).restype = C.c_int
 _lib.q8_version.restype = C.c_char_p
@@ -225,6 +226,26 @@ def q8_embedding_sum3_layernorm(word, pos, typ, scales, wid, pid, tid, gamma, be
                                          float(eps), _ptr(y), _ptr(amax_slots), _ptr(q_scale), _ptr(q_out), _ptr(err_flag),
                                          _stream(stream)),
         "q8_embedding_sum3_layernorm")
+
+
+def q8_attention(qkv, B, S, heads, d, ctx=None, mask=None, scale=None, amax_slots=None, q_scale=None, q_out=None,
+                 stream=None) -> None:
+    """ctx = softmax(scale * Q K^T + mask) V per head on the fused projection output qkv [B*S, 3*heads*d], plus
+    abs-max slots of ctx for the next quantizer, or (stored scale) the int8 codes of ctx themselves."""
+    if qkv.numel() != B * S * 3 * heads * d:
+        raise ValueError("q8_attention: qkv does not hold B*S rows of 3*heads*d columns")
+    if ctx is not None and ctx.numel() != B * S * heads * d:
+        raise ValueError("q8_attention: ctx size mismatch")
+    if q_out is not None and q_out.numel() != B * S * heads * d:
+        raise ValueError("q8_attention: q_out size mismatch")
+    if mask is not None and mask.numel() != B * S:
+        raise ValueError("q8_attention: mask holds one value per (sequence, key)")
+    if amax_slots is not None and amax_slots.numel() < AMAX_SLOTS:
+        raise ValueError("q8_attention: amax_slots holds AMAX_SLOTS floats")
+    if scale is None:
+        scale = 1.0 / float(d) ** 0.5
+    _ck(_lib.q8_attention(_ptr(qkv), B, S, heads, d, _ptr(mask), float(scale), _ptr(ctx), _ptr(amax_slots), _ptr(q_scale),
+                          _ptr(q_out), _stream(stream)), "q8_attention")
 
 
 def raw():

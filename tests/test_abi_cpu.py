@@ -101,6 +101,20 @@ def test_host_side_argument_checks(lib):
     assert lib.q8_layernorm_absmax(p + 2, None, p, p, 1e-12, 1, 4, p, None, None, None, None) == ALIGN
     assert lib.q8_embedding_sum3_layernorm(p, 4, p, 4, p, 4, p, 4, None, p, p, 2, p, p, 1e-12, p, None, None, None, None, None) == NULL
     assert lib.q8_embedding_sum3_layernorm(p, 4, p, 4, p, 4, p, 0, p, p, p, 2, p, p, 1e-12, p, None, None, None, None, None) == SHAPE
+    # FP32 attention between the QKV and attention-output FC layers
+    lib.q8_attention.argtypes = [vp, i64, i64, C.c_int, C.c_int, vp, C.c_float, vp, vp, vp, vp, vp]
+    assert lib.q8_attention(p, -1, 8, 2, 64, None, 0.125, p, None, None, None, None) == SHAPE
+    assert lib.q8_attention(p, 1, 0, 2, 64, None, 0.125, p, None, None, None, None) == SHAPE
+    assert lib.q8_attention(p, 1, 8, 0, 64, None, 0.125, p, None, None, None, None) == SHAPE
+    assert lib.q8_attention(p, 1, 8, 2, 0, None, 0.125, p, None, None, None, None) == SHAPE
+    assert lib.q8_attention(p, 1, 8, 2, 64, None, 0.0, p, None, None, None, None) == SHAPE
+    assert lib.q8_attention(p, 1, 8, 2, 64, None, float("nan"), p, None, None, None, None) == SHAPE
+    assert lib.q8_attention(None, 1, 8, 2, 64, None, 0.125, p, None, None, None, None) == NULL
+    assert lib.q8_attention(p, 1, 8, 2, 64, None, 0.125, None, None, None, None, None) == NULL      # neither ctx nor codes
+    assert lib.q8_attention(p, 1, 8, 2, 64, None, 0.125, p, None, p, None, None) == NULL            # scale without codes
+    assert lib.q8_attention(p + 2, 1, 8, 2, 64, None, 0.125, p, None, None, None, None) == ALIGN
+    assert lib.q8_attention(p, 1, 20000, 2, 48, None, 0.125, p, None, None, None, None) == SHAPE     # generic kernel: S <= 16384
+    assert lib.q8_attention(None, 0, 8, 2, 64, None, 0.125, None, None, None, None, None) in (OK, 5)  # B = 0: nothing to read (no GPU here: launch may be refused)
 
 
 def test_product_package_does_not_reach_the_oracle():

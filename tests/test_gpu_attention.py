@@ -1,0 +1,168 @@
+"""GPU parity of q8_attention against the CPU oracle.  Softmax attention is FP32 glue (Section 3); the GPU
+evaluates it in binary32 (fp32 matrix pipes, running-maximum softmax, exp2), the oracle in binary64.  A score
+is a 64-term binary32 dot product, so its error is a few 1e-7 times its size, the weights inherit that as a
+relative error, and every output -- a convex combination of V rows -- moves by at most that fraction of the
+largest |V| of its head: the bar is |ctx - oracle| <= 1e-5 * max|V| (measured worst case about a tenth of
+it), not the 1e-6 relative of the FC outputs, which an inexact-by-construction fp32 softmax cannot meet
+near zero crossings.  The abs-max slots are exact with respect to the ctx the GPU itself wrote, and int8
+codes follow the stage-wise rule: bit-exact with the oracle's quantization of that ctx."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from oracle import q8_oracle as O  # noqa: E402
+from paper_1910_06188_amd import synth  # noqa: E402
+
+TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def q8():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1910_06188_amd import q8 as mod
+    return mod
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def close(got, ref, vmax):
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64)).max()
+    assert err <= TOL * vmax, f"worst error {err:.3e} = {err / (TOL * vmax):.2f} of the tolerance"
+    return err / (TOL * vmax)
+
+
+def make_mask(g, B, S):
+    """BERT-style padding mask: the tail of each sequence (never token 0) carries -10000."""
+    mask = np.zeros((B, S), np.float32)
+    for b in range(B):
+        keep = int(g.integers(1, S + 1))
+        mask[b, keep:] = -10000.0
+    return mask
+
+
+SHAPES = [  # B, S, heads, d
+    (1, 1, 1, 64), (2, 7, 3, 64), (1, 64, 1, 64), (1, 65, 2, 64), (2, 128, 2, 64), (1, 129, 1, 64), (3, 200, 2, 64),
+    (2, 384, 4, 64), (1, 513, 1, 64),
+    (2, 9, 3, 5), (1, 70, 2, 32), (1, 33, 2, 128), (2, 130, 1, 80),   # other head widths: the generic kernel
+]
+
+
+@pytest.mark.parametrize("B,S,heads,d", SHAPES)
+@pytest.mark.parametrize("with_mask", [False, True])
+def test_attention(q8, B, S, heads, d, with_mask):
+    g = synth.rng(900 + 7 * B + S + 3 * heads + d)
+    HD = heads * d
+    qkv = synth.activations(g, B * S, 3 * HD) * np.float32(1.5)
+    mask = make_mask(g, B, S) if with_mask else None
+    scale = None if (S % 2) else 0.21
+    ref = O.attention(qkv, B, S, heads, d, mask=mask, scale=scale, threads=8)
+    vmax = float(np.abs(qkv[:, 2 * HD:]).max())
+    ctx = torch.full((B * S, HD), 9.0, device="cuda")
+    slots = torch.full((q8.AMAX_SLOTS,), -1.0, device="cuda")
+    q8.q8_attention(dev(qkv), B, S, heads, d, ctx=ctx, mask=None if mask is None else dev(mask), scale=scale, amax_slots=slots)
+    got = host(ctx)
+    close(got, ref, vmax)
+    s = host(slots)
+    assert s.min() >= 0 and s.max() == np.abs(got).max()
+    # the slots feed the quantizer of the attention-output FC: scale and codes follow from the GPU's own ctx
+    q = torch.empty((B * S, HD), dtype=torch.int8, device="cuda")
+    sc, am = torch.zeros(1, device="cuda"), torch.zeros(1, device="cuda")
+    q8.q8_quantize_amax(ctx, slots, sc, q, amax_out=am)
+    assert host(am)[0] == np.abs(got).max() and host(sc)[0] == O.scale(np.abs(got).max())
+    np.testing.assert_array_equal(host(q), O.quantize(got, host(sc)[0]))
+    # stored scale: the same pass writes the codes of its own ctx, with or without storing ctx
+    qs = np.float32(127.0) / np.float32(2.0)
+    qsd = torch.tensor([float(qs)], device="cuda")
+    ctx2 = torch.empty((B * S, HD), device="cuda")
+    q2 = torch.full((B * S, HD), 99, dtype=torch.int8, device="cuda")
+    q8.q8_attention(dev(qkv), B, S, heads, d, ctx=ctx2, mask=None if mask is None else dev(mask), scale=scale, q_scale=qsd, q_out=q2)
+    np.testing.assert_array_equal(host(ctx2), got)
+    np.testing.assert_array_equal(host(q2), O.quantize(got, qs))
+    q3 = torch.full((B * S, HD), 99, dtype=torch.int8, device="cuda")
+    q8.q8_attention(dev(qkv), B, S, heads, d, mask=None if mask is None else dev(mask), scale=scale, q_scale=qsd, q_out=q3)
+    np.testing.assert_array_equal(host(q3), host(q2))
+
+
+def test_attention_sharp_and_flat_softmax(q8):
+    """Scores from near-uniform to near-one-hot rows: the running maximum has to move, and to stay put."""
+    g = synth.rng(77)
+    B, S, heads, d = 2, 200, 2, 64
+    HD = heads * d
+    for gain in (0.05, 1.0, 4.0):
+        qkv = synth.activations(g, B * S, 3 * HD)
+        qkv[:, :2 * HD] *= np.float32(gain)
+        # keys in ascending order of their score against most queries: the maximum changes at every stage
+        qkv[:, HD:2 * HD] *= np.linspace(0.1, 2.0, B * S, dtype=np.float32)[:, None]
+        ref = O.attention(qkv, B, S, heads, d, threads=8)
+        ctx = torch.empty((B * S, HD), device="cuda")
+        q8.q8_attention(dev(qkv), B, S, heads, d, ctx=ctx)
+        close(host(ctx), ref, float(np.abs(qkv[:, 2 * HD:]).max()))
+
+
+def test_attention_closed_forms(q8):
+    g = synth.rng(78)
+    B, S, heads, d = 2, 150, 3, 64
+    HD = heads * d
+    qkv = synth.activations(g, B * S, 3 * HD)
+    qkv[:, :HD] = 0                                      # zero queries: every token gets the mean of V
+    ctx = torch.empty((B * S, HD), device="cuda")
+    q8.q8_attention(dev(qkv), B, S, heads, d, ctx=ctx)
+    v = qkv[:, 2 * HD:].astype(np.float64).reshape(B, S, HD)
+    np.testing.assert_allclose(host(ctx).reshape(B, S, HD), np.repeat(v.mean(axis=1, keepdims=True), S, axis=1), atol=2e-6)
+    mask = np.zeros((B, S), np.float32)
+    mask[:, 40:] = -10000.0                              # ... of the unmasked V rows
+    q8.q8_attention(dev(qkv), B, S, heads, d, ctx=ctx, mask=dev(mask))
+    np.testing.assert_allclose(host(ctx).reshape(B, S, HD), np.repeat(v[:, :40].mean(axis=1, keepdims=True), S, axis=1), atol=2e-6)
+
+
+def test_attention_many_workgroups_and_views(q8):
+    # more workgroups than abs-max slots: the slots are folded with atomics
+    g = synth.rng(79)
+    B, S, heads, d = 33, 16, 64, 64
+    HD = heads * d
+    qkv = synth.activations(g, B * S, 3 * HD)
+    ref = O.attention(qkv, B, S, heads, d, threads=8)
+    ctx = torch.empty((B * S, HD), device="cuda")
+    slots = torch.full((q8.AMAX_SLOTS,), -1.0, device="cuda")
+    q8.q8_attention(dev(qkv), B, S, heads, d, ctx=ctx, amax_slots=slots)
+    got = host(ctx)
+    close(got, ref, float(np.abs(qkv[:, 2 * HD:]).max()))
+    assert host(slots).min() >= 0 and host(slots).max() == np.abs(got).max()
+    # a 4-byte aligned view with d = 64 takes the generic kernel; same bar
+    B, S, heads = 2, 40, 2
+    HD = heads * d
+    qkv = synth.activations(g, B * S, 3 * HD)
+    buf = torch.empty(B * S * 3 * HD + 1, device="cuda")
+    buf[1:] = dev(qkv).reshape(-1)
+    ctx = torch.empty((B * S, HD), device="cuda")
+    q8.q8_attention(buf[1:], B, S, heads, d, ctx=ctx)
+    close(host(ctx), O.attention(qkv, B, S, heads, d), float(np.abs(qkv[:, 2 * HD:]).max()))
+    # B = 0: nothing written, slots cleared
+    slots.fill_(-1.0)
+    q8.q8_attention(torch.empty(0, device="cuda"), 0, 8, 2, 64, ctx=torch.empty(0, device="cuda"), amax_slots=slots)
+    assert (host(slots) == 0).all()
+
+
+def test_attention_bert_large_layer(q8):
+    """The bench shape: 32 sequences of 384 tokens, 16 heads of 64, on the output of a fused QKV projection."""
+    g = synth.rng(80)
+    B, S, heads, d = 32, 384, 16, 64
+    HD = heads * d
+    qkv = synth.activations(g, B * S, 3 * HD)
+    mask = make_mask(g, B, S)
+    ref = O.attention(qkv, B, S, heads, d, mask=mask, threads=16)
+    ctx = torch.empty((B * S, HD), device="cuda")
+    slots = torch.empty((q8.AMAX_SLOTS,), device="cuda")
+    q8.q8_attention(dev(qkv), B, S, heads, d, ctx=ctx, mask=dev(mask), amax_slots=slots)
+    got = host(ctx)
+    close(got, ref, float(np.abs(qkv[:, 2 * HD:]).max()))
+    assert host(slots).max() == np.abs(got).max()
