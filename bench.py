@@ -32,6 +32,7 @@ sys.path.insert(0, ROOT)
 
 METRIC = "int8 TOPS + % MFMA peak on BERT FC GEMMs; tokens/s per quantized BERT layer"
 INT8_PEAK_TOPS = 5033.0      # MI355X published dense int8 matrix peak
+FP32_PEAK_TFLOPS = 157.3    # MI355X published fp32 matrix peak
 HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per launch of the FFN2 GEMM at the default workload, from the two rocprofv3 --pmc runs summarised in
 # profiles/bench_bert_large_layer_pmc_traffic.txt (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, calibrated on a 256 MiB copy)
@@ -225,6 +226,57 @@ class Layer:
         q8.q8_linear(self.gq, self.w_2, self.b_2, s[3:4], self.s_2, self.out)
         q8.q8_layernorm_absmax(self.h1f, self.ln_g, self.ln_b, self.x_next, residual=self.out, q_scale=s[0:1], q_out=self.xq_x)
 
+    def step_layer(self, ev=None):
+        """One whole encoder layer on dynamic scales, every operation in the library: QKV FC, FP32 softmax attention,
+        attention-output FC, residual + LayerNorm, FFN1 (GELU), FFN2, residual + LayerNorm.  Each FP32 operation hands
+        the abs-max of its output to the quantizer of the FC behind it.  Call step_fused() once first (buffers).
+        ev: optional (start, end) event pair recorded around the attention kernel."""
+        q8 = self.q8
+        M, H, F = self.M, self.H, self.F
+        if not hasattr(self, "slots_c"):
+            self.slots_c = self.torch.zeros(q8.AMAX_SLOTS, device="cuda")
+            self.slots_o = self.torch.zeros(q8.AMAX_SLOTS, device="cuda")
+            self.ctx_l = self.torch.empty((M, H), device="cuda")
+        sx = self.scal[1:2]
+        xq = self.xq[: M * H].view(M, H)
+        q8.q8_quantize_amax(self.x_in, self.slots_x, sx, xq)
+        q8.q8_linear(xq, self.w_qkv, self.b_qkv, sx, self.s_qkv, self.qkv, n_groups=3)
+        if ev is not None:
+            ev[0].record()
+        q8.q8_attention(self.qkv, self.batch, self.seq, self.heads, H // self.heads, ctx=self.ctx_l, amax_slots=self.slots_c)
+        if ev is not None:
+            ev[1].record()
+        q8.q8_quantize_amax(self.ctx_l, self.slots_c, sx, xq)
+        q8.q8_linear(xq, self.w_o, self.b_o, sx, self.s_o, self.attn_out)
+        q8.q8_layernorm_absmax(self.x_in, self.ln_g, self.ln_b, self.h1f, residual=self.attn_out, amax_slots=self.slots_h)
+        g_amax, g_scale = self.gscal[0:1], self.gscal[1:2]
+        g_amax.zero_()
+        q8.q8_quantize_amax(self.h1f, self.slots_h, sx, xq)
+        q8.q8_linear(xq, self.w_1, self.b_1, sx, self.s_1, self.g, out_amax=g_amax, flags=q8.EPI_GELU | q8.EPI_ABSMAX)
+        xq2 = self.xq[: M * F].view(M, F)
+        q8.q8_quantize_amax(self.g, g_amax, g_scale, xq2)
+        q8.q8_linear(xq2, self.w_2, self.b_2, g_scale, self.s_2, self.out)
+        q8.q8_layernorm_absmax(self.h1f, self.ln_g, self.ln_b, self.x_next, residual=self.out, amax_slots=self.slots_o)
+
+    def step_layer_static(self):
+        """The whole encoder layer on stored scales (Eq. 4): seven kernels, no quantize pass anywhere -- both LayerNorms
+        and the attention kernel write the int8 codes the next FC reads, FFN1 writes int8 through its epilogue.
+        Call step_fused_static() and step_layer() once first (buffers)."""
+        q8 = self.q8
+        H = self.H
+        s = self.s_static
+        if not hasattr(self, "xq_c"):
+            self.xq_c = self.torch.empty((self.M, H), dtype=self.torch.int8, device="cuda")
+            self.xq_n = self.torch.empty((self.M, H), dtype=self.torch.int8, device="cuda")
+        q8.q8_linear(self.xq_x, self.w_qkv, self.b_qkv, s[0:1], self.s_qkv, self.qkv, n_groups=3)
+        q8.q8_attention(self.qkv, self.batch, self.seq, self.heads, H // self.heads, q_scale=s[1:2], q_out=self.xq_c)
+        q8.q8_linear(self.xq_c, self.w_o, self.b_o, s[1:2], self.s_o, self.attn_out)
+        q8.q8_layernorm_absmax(self.x_in, self.ln_g, self.ln_b, self.h1f, residual=self.attn_out, q_scale=s[2:3], q_out=self.xq_h)
+        q8.q8_linear(self.xq_h, self.w_1, self.b_1, s[2:3], self.s_1, self.gq, next_scale=s[3:4],
+                     flags=q8.EPI_GELU | q8.EPI_REQUANT)
+        q8.q8_linear(self.gq, self.w_2, self.b_2, s[3:4], self.s_2, self.out)
+        q8.q8_layernorm_absmax(self.h1f, self.ln_g, self.ln_b, self.x_next, residual=self.out, q_scale=s[0:1], q_out=self.xq_n)
+
     def glue_once(self):
         """Untimed fp32 glue (attention, residual, LayerNorm) so every FC sees realistic inputs."""
         torch = self.torch
@@ -384,6 +436,36 @@ def main():
     out["fused_layernorm_static_mode"] = {"ms_per_step": round(dtfs * 1e3, 4), "tokens_per_s": round(layer.M / dtfs, 1), "steps": n_static,
                                           "note": "stored scales; the embedding block and both residual+LayerNorm passes also "
                                                   "write the int8 codes of their output, so QKV and FFN1 have no quantize pass"}
+    # the whole encoder layer, FP32 softmax attention included (fp32 matrix pipes: 4 S^2 d flops per head), every
+    # operation in the library -- the layer-level tokens/s; the attention kernel is timed with events inside the step
+    for _ in range(5):
+        layer.step_layer()
+    torch.cuda.synchronize()
+    aev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_static)]
+    t0 = time.perf_counter()
+    for i in range(n_static):
+        layer.step_layer(aev[i])
+    torch.cuda.synchronize()
+    dtl = (time.perf_counter() - t0) / n_static
+    attn_ms = sum(a.elapsed_time(b) for a, b in aev) / n_static
+    attn_flops = 4.0 * layer.batch * layer.heads * layer.seq * layer.seq * (layer.H // layer.heads)
+    out["encoder_layer_mode"] = {"ms_per_step": round(dtl * 1e3, 4), "tokens_per_s": round(layer.M / dtl, 1), "steps": n_static,
+                                 "attention": {"avg_launch_us": round(attn_ms * 1e3, 2), "dtype": "f32",
+                                               "achieved_tflops": round(attn_flops / (attn_ms * 1e-3) / 1e12, 1),
+                                               "frac_of_fp32_mfma_peak": round(attn_flops / (attn_ms * 1e-3) / 1e12 / FP32_PEAK_TFLOPS, 4)},
+                                 "note": "dynamic scales; QKV FC, FP32 softmax attention, attention-output FC, residual + "
+                                         "LayerNorm, FFN1 + GELU, FFN2, residual + LayerNorm; no embedding block"}
+    for _ in range(5):
+        layer.step_layer_static()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n_static):
+        layer.step_layer_static()
+    torch.cuda.synchronize()
+    dtls = (time.perf_counter() - t0) / n_static
+    out["encoder_layer_static_mode"] = {"ms_per_step": round(dtls * 1e3, 4), "tokens_per_s": round(layer.M / dtls, 1), "steps": n_static,
+                                        "note": "stored scales; seven kernels: the attention kernel and both LayerNorms write the "
+                                                "int8 codes the next FC reads, FFN1 writes int8 through its epilogue"}
     # the two FFN GEMMs on their own, launched back to back: once on one set of buffers (operands and output stay in
     # the caches) and once rotating through sets that together exceed the 256 MB Infinity Cache
     def gemm_alone(N, K, flags, int8_out):

@@ -34,7 +34,9 @@ constexpr int kAtKB = 64;                  // keys per stage
 // 4 * 72 = 32 (mod 64) puts the halves on disjoint banks.
 constexpr int kAtKStride = 68;
 constexpr int kAtVStride = 72;
-constexpr int kAtStageFloats = kAtKB * kAtKStride + kAtKB * kAtVStride + kAtKB;  // K tile, V tile, mask row
+constexpr int kAtKTile = kAtKB * kAtKStride;             // floats of a K tile in LDS
+constexpr int kAtVTile = kAtKB * kAtVStride + kAtKB;     // V tile and the stage's mask row
+constexpr int kAtStageFloats = kAtKTile + kAtVTile;
 constexpr int kAtSlots = 2048;             // abs-max slots (= Q8_AMAX_SLOTS)
 
 struct AttnArgs {
@@ -51,9 +53,64 @@ struct AttnArgs {
     float c;              // scale * log2(e)
 };
 
+// S^T block of one stage: s[sub][e] of lane (lq, hi) = <K[32 sub + 8 (e/4) + 4 hi + e%4], c Q[lq]>.  MFMA number
+// 4t + i pairs column 8t + i (lower half-wave) with column 8t + 4 + i (upper half-wave) of both operands.
+__device__ __forceinline__ void attention_scores(const float* Ks, const float (&q)[32], int lq, int hi, v16f (&s)[2])
+{
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[sub][e] = 0.0f;
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            const float4 kf = *reinterpret_cast<const float4*>(Ks + (sub * 32 + lq) * kAtKStride + 4 * hi + 8 * t);
+            s[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.x, q[4 * t + 0], s[sub], 0, 0, 0);
+            s[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.y, q[4 * t + 1], s[sub], 0, 0, 0);
+            s[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.z, q[4 * t + 2], s[sub], 0, 0, 0);
+            s[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.w, q[4 * t + 3], s[sub], 0, 0, 0);
+        }
+}
+
+// Running-maximum softmax step on one stage's scores (log2 units): adds the mask row, moves the maximum,
+// turns s into probabilities relative to the new maximum and returns the factor by which everything
+// accumulated so far shrinks.
+__device__ __forceinline__ float attention_softmax(const float* Ms, int hi, v16f (&s)[2], float& m_run, float& l_run)
+{
+    float mx = -__builtin_inff();
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const float4 mk = *reinterpret_cast<const float4*>(Ms + sub * 32 + 8 * g + 4 * hi);
+            s[sub][4 * g + 0] += mk.x;
+            s[sub][4 * g + 1] += mk.y;
+            s[sub][4 * g + 2] += mk.z;
+            s[sub][4 * g + 3] += mk.w;
+            mx = __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fmaxf(s[sub][4 * g], s[sub][4 * g + 1]),
+                                                     __builtin_fmaxf(s[sub][4 * g + 2], s[sub][4 * g + 3])));
+        }
+    mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
+    // Key 0 of stage 0 is always inside the sequence, so the maximum is finite from the first stage on.
+    const float m_new = __builtin_fmaxf(m_run, mx);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    float psum = 0.0f;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            s[sub][e] = __builtin_amdgcn_exp2f(s[sub][e] - m_new);
+            psum += s[sub][e];
+        }
+    l_run = l_run * alpha + psum;
+    return alpha;
+}
+
 __global__ __launch_bounds__(kAtThreads, 2) void attention_mfma_kernel(AttnArgs a)
 {
-    extern __shared__ __align__(16) float lds[];
+    extern __shared__ __align__(16) float lds[];   // K tiles of two stages, then V tiles (+ mask rows) of two stages
     __shared__ unsigned wave_amax[kAtWaves];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lq = lane & 31, hi = lane >> 5;
@@ -86,37 +143,62 @@ __global__ __launch_bounds__(kAtThreads, 2) void attention_mfma_kernel(AttnArgs 
         }
     }
 
-    // Staging: thread t carries chunks t, t + 256, ... of the 64 x 16 float4 chunks of a K and of a V tile.
+    // Staging: thread t carries chunks t, t + 256, ... of the 64 x 16 float4 chunks of a K and of a V tile
+    // (chunk i: key st_key + 16 i, 16-byte column st_ch).  Offsets within the sequence fit 32 bits (checked
+    // by the launcher).  Fetches and stashes are unconditional -- past the last stage they repeat it into a
+    // tile nobody reads -- so that every trip of the loop is one straight line with all its loads issued at
+    // the top and awaited only at the bottom.
     float4 k0r, k1r, k2r, k3r, v0r, v1r, v2r, v3r;
     float mreg = 0.0f;
-    const int n_stages = (int)((S + kAtKB - 1) / kAtKB);
-    const int st_key = tid >> 4, st_ch = tid & 15;   // chunk i of this thread: key st_key + 16 i, 16-byte column st_ch
-#define Q8_AT_FETCH1(i, kr, vr)                                                              \
-    {                                                                                        \
-        const int64_t row = (k0 + st_key + 16 * (i) < S) ? k0 + st_key + 16 * (i) : S - 1;   \
-        const float4* p = reinterpret_cast<const float4*>(base + row * ld + HD) + st_ch;     \
-        kr = p[0];                                                                           \
-        vr = p[HD / 4];                                                                      \
+    const int S32 = (int)S, ld32 = (int)ld;
+    const int n_stages = (S32 + kAtKB - 1) / kAtKB;
+    const int st_key = tid >> 4, st_ch = tid & 15;
+    const float* const kbase = base + HD;       // K and V of token 0 of this sequence and head (wave-uniform)
+    const float* const vbase = base + 2 * HD;
+    const float* const mrow = a.mask ? a.mask + b * S : nullptr;
+    float* const k_tiles = lds;
+    float* const v_tiles = lds + 2 * kAtKTile;
+    // Offset (in floats, from kbase / vbase) of this thread's chunk i of stage 0, and the offset of the same
+    // column in the last row of the sequence: a stage further on is +64 rows, clamped to that.
+    const unsigned off_last = (unsigned)(S32 - 1) * (unsigned)ld32 + 4u * st_ch;
+    const unsigned off_st0 = (unsigned)st_key * (unsigned)ld32 + 4u * st_ch, off_16 = 16u * (unsigned)ld32;
+    const unsigned off_stage = (unsigned)kAtKB * (unsigned)ld32;
+#define Q8_AT_OFF(stage, i) min(off_st0 + (unsigned)(stage) * off_stage + (unsigned)(i) * off_16, off_last)
+#define Q8_AT_FETCH_K(stage)                                                          \
+    {                                                                                 \
+        k0r = *reinterpret_cast<const float4*>(kbase + Q8_AT_OFF(stage, 0));           \
+        k1r = *reinterpret_cast<const float4*>(kbase + Q8_AT_OFF(stage, 1));           \
+        k2r = *reinterpret_cast<const float4*>(kbase + Q8_AT_OFF(stage, 2));           \
+        k3r = *reinterpret_cast<const float4*>(kbase + Q8_AT_OFF(stage, 3));           \
     }
-#define Q8_AT_FETCH(stage)                                                                   \
-    {                                                                                        \
-        const int64_t k0 = (int64_t)(stage) * kAtKB;                                         \
-        Q8_AT_FETCH1(0, k0r, v0r) Q8_AT_FETCH1(1, k1r, v1r) Q8_AT_FETCH1(2, k2r, v2r) Q8_AT_FETCH1(3, k3r, v3r) \
-        if (tid < kAtKB) {                                                                   \
-            const int64_t key = k0 + tid;                                                    \
-            /* beyond the sequence: -inf, the key gets weight 0 whatever its (repeated) row holds */ \
-            mreg = (key < S) ? (a.mask ? a.mask[b * S + key] * 1.44269504088896341f : 0.0f) : -__builtin_inff(); \
-        }                                                                                    \
+#define Q8_AT_FETCH_V(stage)                                                          \
+    {                                                                                 \
+        v0r = *reinterpret_cast<const float4*>(vbase + Q8_AT_OFF(stage, 0));           \
+        v1r = *reinterpret_cast<const float4*>(vbase + Q8_AT_OFF(stage, 1));           \
+        v2r = *reinterpret_cast<const float4*>(vbase + Q8_AT_OFF(stage, 2));           \
+        v3r = *reinterpret_cast<const float4*>(vbase + Q8_AT_OFF(stage, 3));           \
+        if (mrow) mreg = mrow[min((stage) * kAtKB + (tid & 63), S32 - 1)];             \
     }
-#define Q8_AT_STASH1(i, kr, vr)                                                              \
-    *reinterpret_cast<float4*>(Ks_w + (st_key + 16 * (i)) * kAtKStride + 4 * st_ch) = kr;    \
-    *reinterpret_cast<float4*>(Vs_w + (st_key + 16 * (i)) * kAtVStride + 4 * st_ch) = vr;
-#define Q8_AT_STASH(buf)                                                                     \
-    {                                                                                        \
-        float* Ks_w = lds + (buf) * kAtStageFloats;                                          \
-        float* Vs_w = Ks_w + kAtKB * kAtKStride;                                             \
-        Q8_AT_STASH1(0, k0r, v0r) Q8_AT_STASH1(1, k1r, v1r) Q8_AT_STASH1(2, k2r, v2r) Q8_AT_STASH1(3, k3r, v3r) \
-        if (tid < kAtKB) Vs_w[kAtKB * kAtVStride + tid] = mreg;                              \
+#define Q8_AT_STASH_K(buf)                                                            \
+    {                                                                                 \
+        float* w = k_tiles + (buf) * kAtKTile + st_key * kAtKStride + 4 * st_ch;      \
+        *reinterpret_cast<float4*>(w) = k0r;                                          \
+        *reinterpret_cast<float4*>(w + 16 * kAtKStride) = k1r;                        \
+        *reinterpret_cast<float4*>(w + 32 * kAtKStride) = k2r;                        \
+        *reinterpret_cast<float4*>(w + 48 * kAtKStride) = k3r;                        \
+    }
+    // the mask row goes in with the V tile, in log2 units; beyond the sequence -inf: weight 0 whatever the
+    // (repeated) row holds
+#define Q8_AT_STASH_V(buf, stage)                                                     \
+    {                                                                                 \
+        float* w = v_tiles + (buf) * kAtVTile + st_key * kAtVStride + 4 * st_ch;      \
+        *reinterpret_cast<float4*>(w) = v0r;                                          \
+        *reinterpret_cast<float4*>(w + 16 * kAtVStride) = v1r;                        \
+        *reinterpret_cast<float4*>(w + 32 * kAtVStride) = v2r;                        \
+        *reinterpret_cast<float4*>(w + 48 * kAtVStride) = v3r;                        \
+        if (tid < kAtKB)                                                              \
+            v_tiles[(buf) * kAtVTile + kAtKB * kAtVStride + tid] =                    \
+                ((stage) * kAtKB + tid < S32) ? mreg * 1.44269504088896341f : -__builtin_inff(); \
     }
 
     v16f o[2];           // O^T: o[blk][e] = ctx[query lq][column 32 blk + 8 (e/4) + 4 hi + e%4], not yet normalised
@@ -125,62 +207,35 @@ __global__ __launch_bounds__(kAtThreads, 2) void attention_mfma_kernel(AttnArgs 
     float m_run = -__builtin_inff();   // running maximum of this lane's query (log2 units), same in both half-waves
     float l_run = 0.0f;                // this lane's share of the running denominator
 
-    Q8_AT_FETCH(0)
-    Q8_AT_STASH(0)
+    // The loop is skewed by one stage: trip st forms the scores of stage st + 1 on the matrix pipe while the
+    // vector ALU runs the softmax of stage st, then accumulates P V of stage st.  So K runs one stage ahead
+    // of V in LDS, and two ahead in the staging registers.
+    v16f s_cur[2], s_nxt[2];
+    const int last = n_stages - 1;
+    Q8_AT_FETCH_K(0)
+    Q8_AT_STASH_K(0)
+    Q8_AT_FETCH_V(0)
+    Q8_AT_FETCH_K(min(1, last))
+    __syncthreads();
+    attention_scores(k_tiles, q, lq, hi, s_cur);
+    Q8_AT_STASH_V(0, 0)
+    Q8_AT_STASH_K(1)
     __syncthreads();
 
     for (int st = 0; st < n_stages; ++st) {
-        const bool more = st + 1 < n_stages;
-        if (more) Q8_AT_FETCH(st + 1)
-        const float* Ks = lds + (st & 1) * kAtStageFloats;
-        const float* Vs = Ks + kAtKB * kAtKStride;
+        const bool more = st < last;
+        const int nv = min(st + 1, last), nk = min(st + 2, last);
+        Q8_AT_FETCH_V(nv)
+        Q8_AT_FETCH_K(nk)
+        const float* Vs = v_tiles + (st & 1) * kAtVTile;
         const float* Ms = Vs + kAtKB * kAtVStride;
-
-        // S^T = K Q^T for the two 32-key blocks of the stage.  MFMA number 4t + i pairs column 8t + i
-        // (lower half-wave) with column 8t + 4 + i (upper half-wave) of both operands.
-        v16f s[2];
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) s[sub][e] = 0.0f;
-            const float* krow = Ks + (sub * 32 + lq) * kAtKStride + 4 * hi;
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                const float4 kf = *reinterpret_cast<const float4*>(krow + 8 * t);
-                s[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.x, q[4 * t + 0], s[sub], 0, 0, 0);
-                s[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.y, q[4 * t + 1], s[sub], 0, 0, 0);
-                s[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.z, q[4 * t + 2], s[sub], 0, 0, 0);
-                s[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.w, q[4 * t + 3], s[sub], 0, 0, 0);
-            }
+        float alpha;
+        if (more) {
+            attention_scores(k_tiles + ((st + 1) & 1) * kAtKTile, q, lq, hi, s_nxt);
+            alpha = attention_softmax(Ms, hi, s_cur, m_run, l_run);
+        } else {
+            alpha = attention_softmax(Ms, hi, s_cur, m_run, l_run);
         }
-        // s[sub][e] of lane (lq, hi) is the score of query lq against key 32 sub + 8 (e/4) + 4 hi + e%4.
-        float mx = -__builtin_inff();
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const float4 mk = *reinterpret_cast<const float4*>(Ms + sub * 32 + 8 * g + 4 * hi);
-                s[sub][4 * g + 0] += mk.x;
-                s[sub][4 * g + 1] += mk.y;
-                s[sub][4 * g + 2] += mk.z;
-                s[sub][4 * g + 3] += mk.w;
-                mx = __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fmaxf(s[sub][4 * g], s[sub][4 * g + 1]),
-                                                         __builtin_fmaxf(s[sub][4 * g + 2], s[sub][4 * g + 3])));
-            }
-        mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
-        // Key 0 of stage 0 is always inside the sequence, so the maximum is finite from the first stage on.
-        const float m_new = __builtin_fmaxf(m_run, mx);
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
-        float psum = 0.0f;
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                s[sub][e] = __builtin_amdgcn_exp2f(s[sub][e] - m_new);
-                psum += s[sub][e];
-            }
-        l_run = l_run * alpha + psum;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             o[0][e] *= alpha;
@@ -193,11 +248,14 @@ __global__ __launch_bounds__(kAtThreads, 2) void attention_mfma_kernel(AttnArgs 
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const float* vrow = Vs + (sub * 32 + 8 * (e >> 2) + 4 * hi + (e & 3)) * kAtVStride + lq;
-                o[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[0], s[sub][e], o[0], 0, 0, 0);
-                o[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[32], s[sub][e], o[1], 0, 0, 0);
+                o[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[0], s_cur[sub][e], o[0], 0, 0, 0);
+                o[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[32], s_cur[sub][e], o[1], 0, 0, 0);
             }
-        if (more) Q8_AT_STASH((st + 1) & 1)
+        Q8_AT_STASH_V((st + 1) & 1, nv)
+        Q8_AT_STASH_K(st & 1)
         __syncthreads();
+        s_cur[0] = s_nxt[0];
+        s_cur[1] = s_nxt[1];
     }
 
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -297,10 +355,11 @@ __global__ __launch_bounds__(64) void attention_generic_kernel(const float* __re
     }
 }
 
-#undef Q8_AT_FETCH1
-#undef Q8_AT_FETCH
-#undef Q8_AT_STASH1
-#undef Q8_AT_STASH
+#undef Q8_AT_OFF
+#undef Q8_AT_FETCH_K
+#undef Q8_AT_FETCH_V
+#undef Q8_AT_STASH_K
+#undef Q8_AT_STASH_V
 
 __global__ void attention_slots_clear_kernel(unsigned* slots)
 {
@@ -314,8 +373,9 @@ int attention_generic_max_s() { return 16384; }   // scores of one query in 64 K
 bool attention_mfma_eligible(const float* qkv, int64_t B, int64_t S, int heads, int d, const float* ctx, const int8_t* q_out)
 {
     const int64_t wgs = B * heads * ((S + kAtQB - 1) / kAtQB);
+    // 32-bit arithmetic inside: the workgroup count, and offsets within one sequence of qkv
     return d == kAtD && at_aligned(qkv, 16) && (!ctx || at_aligned(ctx, 16)) && at_aligned(q_out, 4) &&
-           wgs < ((int64_t)1 << 31);
+           wgs < ((int64_t)1 << 31) && S * 3 * heads * kAtD < ((int64_t)1 << 31);
 }
 
 int launch_attention(const float* qkv, int64_t B, int64_t S, int heads, int d, const float* mask, float scale, float* ctx,
