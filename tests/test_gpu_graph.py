@@ -66,3 +66,65 @@ def test_dynamic_ffn_chain_under_graph_capture(q8):
         torch.cuda.synchronize()
         assert torch.equal(y_graph, y) and torch.equal(g_graph, g) and torch.equal(s_graph, gs), rep
         assert float(y.abs().max()) > 0
+
+
+def test_attention_block_under_graph_capture(q8):
+    """LayerNorm (abs-max slots) -> quantize -> fused QKV FC -> FP32 attention (abs-max slots) -> quantize ->
+    attention-output FC -> residual + LayerNorm: the first half of an encoder layer, captured and replayed."""
+    B, S, heads, d = 3, 100, 2, 64
+    M, H = B * S, heads * d
+    g = synth.rng(21)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    def quant_w(W):
+        wd, a, s = dev(W), torch.zeros(1, device="cuda"), torch.zeros(1, device="cuda")
+        q8.q8_absmax(wd, a, s)
+        wq = torch.empty(W.shape, dtype=torch.int8, device="cuda")
+        q8.q8_quantize(wd, s, wq)
+        return wq, s
+    parts = [quant_w(synth.weights(g, H, H) * np.float32(4.0)) for _ in range(3)]
+    w_qkv = torch.cat([p[0] for p in parts], 0).contiguous()
+    s_qkv = torch.cat([p[1] for p in parts]).contiguous()
+    b_qkv = dev(synth.weights(g, 1, 3 * H)[0])
+    w_o, s_o = quant_w(synth.weights(g, H, H))
+    b_o = dev(synth.weights(g, 1, H)[0])
+    gamma, beta = torch.ones(H, device="cuda"), torch.zeros(H, device="cuda")
+    mask = np.zeros((B, S), np.float32)
+    mask[1, 70:] = -10000.0
+    mask_d = dev(mask)
+    x = dev(synth.activations(g, M, H))
+    x_ln, qkv, ctx, attn, y = (torch.empty((M, n), device="cuda") for n in (H, 3 * H, H, H, H))
+    xq = torch.empty((M, H), dtype=torch.int8, device="cuda")
+    slots_a, slots_b, slots_c = (torch.zeros(q8.AMAX_SLOTS, device="cuda") for _ in range(3))
+    sx = torch.zeros(1, device="cuda")
+
+    def chain():
+        q8.q8_layernorm_absmax(x, gamma, beta, x_ln, amax_slots=slots_a)
+        q8.q8_quantize_amax(x_ln, slots_a, sx, xq)
+        q8.q8_linear(xq, w_qkv, b_qkv, sx, s_qkv, qkv, n_groups=3)
+        q8.q8_attention(qkv, B, S, heads, d, ctx=ctx, mask=mask_d, amax_slots=slots_b)
+        q8.q8_quantize_amax(ctx, slots_b, sx, xq)
+        q8.q8_linear(xq, w_o, b_o, sx, s_o, attn)
+        q8.q8_layernorm_absmax(x_ln, gamma, beta, y, residual=attn, amax_slots=slots_c)
+
+    chain()                                    # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            chain()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        x.copy_(dev(synth.activations(g, M, H) * np.float32(0.5 + rep)))
+        y.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (y, ctx, qkv, slots_b, slots_c)]
+        y.zero_()
+        ctx.zero_()
+        chain()                                # eager, on the same input
+        torch.cuda.synchronize()
+        for a, b in zip(got, (y, ctx, qkv, slots_b, slots_c)):
+            assert torch.equal(a, b), rep
+        assert float(y.abs().max()) > 0
