@@ -73,39 +73,102 @@ __device__ __forceinline__ void attention_scores(const float* Ks, const float (&
         }
 }
 
-// Running-maximum softmax step on one stage's scores (log2 units): adds the mask row, moves the maximum,
-// turns s into probabilities relative to the new maximum and returns the factor by which everything
-// accumulated so far shrinks.
-__device__ __forceinline__ float attention_softmax(const float* Ms, int hi, v16f (&s)[2], float& m_run, float& l_run)
+// One trip of the key loop, skewed by a stage: the vector ALU runs the running-maximum softmax of the
+// current stage's scores `sc` (log2 units; mask row Ms) while -- kMore -- the matrix pipe forms the next stage's
+// scores `sn` from the K tile Kn; then O^T += V^T P^T of the current stage.  The two instruction streams are
+// cut into eight chunks each and issued chunk by chunk (scheduling fences in between): a wave issues in
+// order, so softmax arithmetic placed behind a block of MFMAs would wait for the block to drain into the
+// pipe, and MFMAs placed behind the arithmetic would leave the pipe empty meanwhile.
+//   chunks 0-2: add the mask row, row maximum of this lane's 32 scores; then the exchange between half-waves
+//   chunk  3  : new running maximum m, shrink factor alpha = 2^(m_old - m) of everything accumulated so far
+//   chunks 3-7: p = 2^(s - m), their sum, and O *= alpha (the P V MFMAs of the previous trip are long done)
+template <bool kMore>
+__device__ __forceinline__ void attention_trip(const float* Kn, const float* Vs, const float* Ms, const float (&q)[32], int lq,
+                                               int hi, v16f (&sc)[2], v16f (&sn)[2], v16f (&o)[2], float& m_run, float& l_run)
 {
-    float mx = -__builtin_inff();
+    if (kMore) {
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
+        for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const float4 mk = *reinterpret_cast<const float4*>(Ms + sub * 32 + 8 * g + 4 * hi);
-            s[sub][4 * g + 0] += mk.x;
-            s[sub][4 * g + 1] += mk.y;
-            s[sub][4 * g + 2] += mk.z;
-            s[sub][4 * g + 3] += mk.w;
-            mx = __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fmaxf(s[sub][4 * g], s[sub][4 * g + 1]),
-                                                     __builtin_fmaxf(s[sub][4 * g + 2], s[sub][4 * g + 3])));
+            for (int e = 0; e < 16; ++e) sn[sub][e] = 0.0f;
+    }
+    float mx = -__builtin_inff(), mx_other = 0.0f, m_new = 0.0f, alpha = 1.0f, psum = 0.0f;
+    constexpr int exp_end[8] = {0, 0, 0, 4, 11, 18, 25, 32};   // p[0 .. exp_end[t]) are done after chunk t
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        if (kMore) {
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+                const float4 kf = *reinterpret_cast<const float4*>(Kn + (sub * 32 + lq) * kAtKStride + 4 * hi + 8 * t);
+                sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.x, q[4 * t + 0], sn[sub], 0, 0, 0);
+                sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.y, q[4 * t + 1], sn[sub], 0, 0, 0);
+                sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.z, q[4 * t + 2], sn[sub], 0, 0, 0);
+                sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.w, q[4 * t + 3], sn[sub], 0, 0, 0);
+            }
         }
-    mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
-    // Key 0 of stage 0 is always inside the sequence, so the maximum is finite from the first stage on.
-    const float m_new = __builtin_fmaxf(m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    m_run = m_new;
-    float psum = 0.0f;
+        if (t < 3) {
+#pragma unroll
+            for (int grp = 3 * t; grp < (t == 2 ? 8 : 3 * t + 3); ++grp) {   // group = 4 consecutive keys: (sub, g)
+                const int sub = grp >> 2, g = grp & 3;
+                const float4 mk = *reinterpret_cast<const float4*>(Ms + sub * 32 + 8 * g + 4 * hi);
+                sc[sub][4 * g + 0] += mk.x;
+                sc[sub][4 * g + 1] += mk.y;
+                sc[sub][4 * g + 2] += mk.z;
+                sc[sub][4 * g + 3] += mk.w;
+                mx = __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fmaxf(sc[sub][4 * g], sc[sub][4 * g + 1]),
+                                                         __builtin_fmaxf(sc[sub][4 * g + 2], sc[sub][4 * g + 3])));
+            }
+            if (t == 2) mx_other = __shfl_xor(mx, 32, 64);
+        } else {
+            if (t == 3) {
+                // Key 0 of stage 0 is always inside the sequence, so the maximum is finite from the first stage on.
+                m_new = __builtin_fmaxf(m_run, __builtin_fmaxf(mx, mx_other));
+                alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+                m_run = m_new;
+            }
+#pragma unroll
+            for (int i = exp_end[t - 1]; i < exp_end[t]; ++i) {
+                sc[i >> 4][i & 15] = __builtin_amdgcn_exp2f(sc[i >> 4][i & 15] - m_new);
+                psum += sc[i >> 4][i & 15];
+            }
+            if (t >= 4) {
+#pragma unroll
+                for (int e = 4 * (t - 4); e < 4 * (t - 4) + 4; ++e) {
+                    o[0][e] *= alpha;
+                    o[1][e] *= alpha;
+                }
+            }
+        }
+        if (kMore) {   // issue order within the chunk: the LDS reads, then one MFMA, four vector instructions, one MFMA, ...
+            __builtin_amdgcn_sched_group_barrier(0x100, 5, 0);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x402, 4, 0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    l_run = l_run * alpha + psum;
+    // O^T += V^T P^T: MFMA (sub, e) pairs key 32 sub + 8 (e/4) + e%4 (lower half-wave) with the key four
+    // further on (upper half-wave) -- the keys whose probabilities the two halves hold in register e.
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            s[sub][e] = __builtin_amdgcn_exp2f(s[sub][e] - m_new);
-            psum += s[sub][e];
+            const float* vrow = Vs + (sub * 32 + 8 * (e >> 2) + 4 * hi + (e & 3)) * kAtVStride + lq;
+            o[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[0], sc[sub][e], o[0], 0, 0, 0);
+            o[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[32], sc[sub][e], o[1], 0, 0, 0);
         }
-    l_run = l_run * alpha + psum;
-    return alpha;
+    // issue order: V operands are read three MFMA pairs ahead of their use, so no MFMA waits for LDS
+    __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+#pragma unroll
+    for (int i = 0; i < 29; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
+    __builtin_amdgcn_sched_barrier(0);
 }
 
 __global__ __launch_bounds__(kAtThreads, 2) void attention_mfma_kernel(AttnArgs a)
@@ -229,28 +292,10 @@ __global__ __launch_bounds__(kAtThreads, 2) void attention_mfma_kernel(AttnArgs 
         Q8_AT_FETCH_K(nk)
         const float* Vs = v_tiles + (st & 1) * kAtVTile;
         const float* Ms = Vs + kAtKB * kAtVStride;
-        float alpha;
-        if (more) {
-            attention_scores(k_tiles + ((st + 1) & 1) * kAtKTile, q, lq, hi, s_nxt);
-            alpha = attention_softmax(Ms, hi, s_cur, m_run, l_run);
-        } else {
-            alpha = attention_softmax(Ms, hi, s_cur, m_run, l_run);
-        }
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            o[0][e] *= alpha;
-            o[1][e] *= alpha;
-        }
-        // O^T += V^T P^T: MFMA (sub, e) pairs key 32 sub + 8 (e/4) + e%4 (lower half-wave) with the key four
-        // further on (upper half-wave) -- the keys whose probabilities the two halves hold in register e.
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const float* vrow = Vs + (sub * 32 + 8 * (e >> 2) + 4 * hi + (e & 3)) * kAtVStride + lq;
-                o[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[0], s_cur[sub][e], o[0], 0, 0, 0);
-                o[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[32], s_cur[sub][e], o[1], 0, 0, 0);
-            }
+        if (more)
+            attention_trip<true>(k_tiles + ((st + 1) & 1) * kAtKTile, Vs, Ms, q, lq, hi, s_cur, s_nxt, o, m_run, l_run);
+        else
+            attention_trip<false>(k_tiles, Vs, Ms, q, lq, hi, s_cur, s_nxt, o, m_run, l_run);
         Q8_AT_STASH_V((st + 1) & 1, nv)
         Q8_AT_STASH_K(st & 1)
         __syncthreads();
