@@ -3,9 +3,10 @@ evaluates it in binary32 (fp32 matrix pipes, running-maximum softmax, exp2), the
 is a 64-term binary32 dot product, so its error is a few 1e-7 times its size, the weights inherit that as a
 relative error, and every output -- a convex combination of V rows -- moves by at most that fraction of the
 largest |V| of its head: the bar is |ctx - oracle| <= 1e-5 * max|V| (measured: 0.02-0.08 of it on
-unit-variance inputs, 0.4 of it when the scores reach +-100), not the 1e-6 relative of the FC outputs, which an inexact-by-construction fp32 softmax cannot meet
-near zero crossings.  The abs-max slots are exact with respect to the ctx the GPU itself wrote, and int8
-codes follow the stage-wise rule: bit-exact with the oracle's quantization of that ctx."""
+unit-variance inputs, 0.4 of it when the scores reach +-100), not the 1e-6 relative of the FC outputs, which
+an fp32 softmax cannot meet near the zero crossings of its outputs.  The abs-max slots are exact with respect
+to the ctx the GPU itself wrote, and int8 codes follow the stage-wise rule: bit-exact with the oracle's
+quantization of that ctx."""
 import numpy as np
 import pytest
 
