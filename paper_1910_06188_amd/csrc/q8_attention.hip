@@ -190,22 +190,6 @@ __global__ __launch_bounds__(kAtThreads, 2) void attention_mfma_kernel(AttnArgs 
     const float* base = a.qkv + b * S * ld + (int64_t)h * kAtD;   // Q of token 0 of this sequence and head
     const int64_t q0 = (int64_t)qb * kAtQB + wave * kAtQW;
 
-    // The wave's queries: lane (lq, hi) holds, for t = 0..7, columns 8t + 4hi .. 8t + 4hi + 3 of query lq.
-    // A row beyond the sequence repeats the last one (computed, never stored).
-    float q[32];
-    {
-        const int64_t qrow = (q0 + lq < S) ? q0 + lq : S - 1;
-        const float4* qp = reinterpret_cast<const float4*>(base + qrow * ld) + hi;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const float4 v = qp[2 * t];
-            q[4 * t + 0] = v.x * a.c;
-            q[4 * t + 1] = v.y * a.c;
-            q[4 * t + 2] = v.z * a.c;
-            q[4 * t + 3] = v.w * a.c;
-        }
-    }
-
     // Staging: thread t carries chunks t, t + 256, ... of the 64 x 16 float4 chunks of a K and of a V tile
     // (chunk i: key st_key + 16 i, 16-byte column st_ch).  Offsets within the sequence fit 32 bits (checked
     // by the launcher).  Fetches and stashes are unconditional -- past the last stage they repeat it into a
@@ -276,9 +260,27 @@ __global__ __launch_bounds__(kAtThreads, 2) void attention_mfma_kernel(AttnArgs 
     v16f s_cur[2], s_nxt[2];
     const int last = n_stages - 1;
     Q8_AT_FETCH_K(0)
+    // The wave's queries, requested behind the first K tile so that the two latencies overlap: lane (lq, hi)
+    // holds, for t = 0..7, columns 8t + 4hi .. 8t + 4hi + 3 of query lq, times scale * log2 e.  A row beyond
+    // the sequence repeats the last one (computed, never stored).
+    float q[32];
+    float4 qraw[8];
+    {
+        const int64_t qrow = (q0 + lq < S) ? q0 + lq : S - 1;
+        const float4* qp = reinterpret_cast<const float4*>(base + qrow * ld) + hi;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) qraw[t] = qp[2 * t];
+    }
     Q8_AT_STASH_K(0)
     Q8_AT_FETCH_V(0)
     Q8_AT_FETCH_K(min(1, last))
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        q[4 * t + 0] = qraw[t].x * a.c;
+        q[4 * t + 1] = qraw[t].y * a.c;
+        q[4 * t + 2] = qraw[t].z * a.c;
+        q[4 * t + 3] = qraw[t].w * a.c;
+    }
     __syncthreads();
     attention_scores(k_tiles, q, lq, hi, s_cur);
     Q8_AT_STASH_V(0, 0)
