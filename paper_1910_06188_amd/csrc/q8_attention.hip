@@ -73,70 +73,160 @@ __device__ __forceinline__ void attention_scores(const float* Ks, const float (&
         }
 }
 
+// Global -> registers -> LDS staging of the K and V tiles (and the mask row) of a stage.  Thread t carries chunks
+// t, t + 256, ... of the 64 x 16 float4 chunks of a tile: chunk i is key st_key + 16 i, 16-byte column st_ch.
+// Offsets within the sequence fit 32 bits (checked by the launcher); rows beyond the sequence repeat the last one.
+struct AttnStager {
+    const float *kbase, *vbase;   // K and V of token 0 of this sequence and head (wave-uniform)
+    const float* mrow;            // mask row of the sequence, or null
+    float *k_tiles, *v_tiles;     // two K tiles; two (V tile + mask row)
+    unsigned off_st0, off_16, off_stage, off_last;
+    int S32, tid, st_key, st_ch;
+    float4 k0, k1, k2, k3, v0, v1, v2, v3;
+    float m;
+
+    __device__ __forceinline__ unsigned off(int stage, int i) const
+    {
+        return min(off_st0 + (unsigned)stage * off_stage + (unsigned)i * off_16, off_last);
+    }
+    __device__ __forceinline__ static float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+    __device__ __forceinline__ void fetch_k01(int stage) { k0 = ld4(kbase + off(stage, 0)); k1 = ld4(kbase + off(stage, 1)); }
+    __device__ __forceinline__ void fetch_k23(int stage) { k2 = ld4(kbase + off(stage, 2)); k3 = ld4(kbase + off(stage, 3)); }
+    __device__ __forceinline__ void fetch_v01(int stage) { v0 = ld4(vbase + off(stage, 0)); v1 = ld4(vbase + off(stage, 1)); }
+    __device__ __forceinline__ void fetch_v23(int stage)
+    {
+        v2 = ld4(vbase + off(stage, 2));
+        v3 = ld4(vbase + off(stage, 3));
+        if (mrow) m = mrow[min(stage * kAtKB + (tid & 63), S32 - 1)];
+    }
+    __device__ __forceinline__ void stash_k(int buf) const
+    {
+        float* w = k_tiles + buf * kAtKTile + st_key * kAtKStride + 4 * st_ch;
+        *reinterpret_cast<float4*>(w) = k0;
+        *reinterpret_cast<float4*>(w + 16 * kAtKStride) = k1;
+        *reinterpret_cast<float4*>(w + 32 * kAtKStride) = k2;
+        *reinterpret_cast<float4*>(w + 48 * kAtKStride) = k3;
+    }
+    // One LDS store of the stash that follows trip st: pieces 0-3 the V tile of stage st + 1, 4-7 the K tile
+    // fetched during that trip, 8 the mask row of stage st + 1.
+    __device__ __forceinline__ void stash_piece(int j, int st) const
+    {
+        if (j < 4) {
+            const float4 v = j == 0 ? v0 : j == 1 ? v1 : j == 2 ? v2 : v3;
+            *reinterpret_cast<float4*>(v_tiles + ((st + 1) & 1) * kAtVTile + (st_key + 16 * j) * kAtVStride + 4 * st_ch) = v;
+        } else if (j < 8) {
+            const float4 k = j == 4 ? k0 : j == 5 ? k1 : j == 6 ? k2 : k3;
+            *reinterpret_cast<float4*>(k_tiles + (st & 1) * kAtKTile + (st_key + 16 * (j - 4)) * kAtKStride + 4 * st_ch) = k;
+        } else if (tid < kAtKB) {
+            v_tiles[((st + 1) & 1) * kAtVTile + kAtKB * kAtVStride + tid] =
+                ((st + 1) * kAtKB + tid < S32) ? m * 1.44269504088896341f : -__builtin_inff();
+        }
+    }
+    // the mask row goes in with the V tile, in log2 units; beyond the sequence -inf: weight 0 whatever the
+    // (repeated) row holds
+    __device__ __forceinline__ void stash_v(int buf, int stage) const
+    {
+        float* w = v_tiles + buf * kAtVTile + st_key * kAtVStride + 4 * st_ch;
+        *reinterpret_cast<float4*>(w) = v0;
+        *reinterpret_cast<float4*>(w + 16 * kAtVStride) = v1;
+        *reinterpret_cast<float4*>(w + 32 * kAtVStride) = v2;
+        *reinterpret_cast<float4*>(w + 48 * kAtVStride) = v3;
+        if (tid < kAtKB)
+            v_tiles[buf * kAtVTile + kAtKB * kAtVStride + tid] =
+                (stage * kAtKB + tid < S32) ? m * 1.44269504088896341f : -__builtin_inff();
+    }
+};
+
 // One trip of the key loop, skewed by a stage: the vector ALU runs the running-maximum softmax of the
 // current stage's scores `sc` (log2 units; mask row Ms) while -- kMore -- the matrix pipe forms the next stage's
-// scores `sn` from the K tile Kn; then O^T += V^T P^T of the current stage.  The two instruction streams are
-// cut into eight chunks each and issued chunk by chunk (scheduling fences in between): a wave issues in
-// order, so softmax arithmetic placed behind a block of MFMAs would wait for the block to drain into the
-// pipe, and MFMAs placed behind the arithmetic would leave the pipe empty meanwhile.
-//   chunks 0-2: add the mask row, row maximum of this lane's 32 scores; then the exchange between half-waves
+// scores `sn` from the K tile Kn; then O^T += V^T P^T of the current stage.  A wave issues in order, so anything
+// that waits (an LDS read used at once, a block of address arithmetic and loads, arithmetic behind a run of
+// MFMAs) stops its MFMAs as well.  The streams are therefore cut into eight chunks issued in a fixed pattern
+// (scheduling groups): every chunk first requests what the NEXT chunk needs from LDS, then alternates one
+// MFMA with a few vector instructions.
+//   chunks 1-3: add the mask row, row maximum of this lane's 32 scores; exchange between the half-waves
 //   chunk  3  : new running maximum m, shrink factor alpha = 2^(m_old - m) of everything accumulated so far
-//   chunks 3-7: p = 2^(s - m), their sum, and O *= alpha (the P V MFMAs of the previous trip are long done)
+//   chunks 4-7: p = 2^(s - m), their sum, and O *= alpha (the P V MFMAs of the previous trip are long done)
+//   chunks 0-3: the tile fetches of the stages ahead (V of stage st + 1, K of stage nk), two loads per chunk:
+//               issued between MFMAs they cost the matrix pipe nothing, issued in a block they stop it
 template <bool kMore>
 __device__ __forceinline__ void attention_trip(const float* Kn, const float* Vs, const float* Ms, const float (&q)[32], int lq,
-                                               int hi, v16f (&sc)[2], v16f (&sn)[2], v16f (&o)[2], float& m_run, float& l_run)
+                                               int hi, v16f (&sc)[2], v16f (&sn)[2], v16f (&o)[2], float& m_run, float& l_run,
+                                               AttnStager& sg, int st, int nk)
 {
+    float mx = -__builtin_inff(), m_new = 0.0f, alpha = 1.0f, psum = 0.0f;
+    const float* krow = Kn + lq * kAtKStride + 4 * hi;     // sub-block 1 is 32 rows further on
+    const float* mrow = Ms + 4 * hi;
+    float4 kf[2], kf_next[2], mk[3], mk_next[3];
     if (kMore) {
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
+        for (int sub = 0; sub < 2; ++sub) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) sn[sub][e] = 0.0f;
+            kf[sub] = *reinterpret_cast<const float4*>(krow + sub * 32 * kAtKStride);
+        }
     }
-    float mx = -__builtin_inff(), mx_other = 0.0f, m_new = 0.0f, alpha = 1.0f, psum = 0.0f;
-    constexpr int exp_end[8] = {0, 0, 0, 4, 11, 18, 25, 32};   // p[0 .. exp_end[t]) are done after chunk t
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
-        if (kMore) {
+        // LDS requests for the next chunk: its K fragments, and the mask values of its key groups
+        // (group = 4 consecutive keys (sub, g); chunk c in 1..3 handles groups 3(c-1) .. min(3c, 8) - 1)
+        if (kMore && t < 7) {
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub) {
-                const float4 kf = *reinterpret_cast<const float4*>(Kn + (sub * 32 + lq) * kAtKStride + 4 * hi + 8 * t);
-                sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.x, q[4 * t + 0], sn[sub], 0, 0, 0);
-                sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.y, q[4 * t + 1], sn[sub], 0, 0, 0);
-                sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.z, q[4 * t + 2], sn[sub], 0, 0, 0);
-                sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf.w, q[4 * t + 3], sn[sub], 0, 0, 0);
-            }
+            for (int sub = 0; sub < 2; ++sub)
+                kf_next[sub] = *reinterpret_cast<const float4*>(krow + sub * 32 * kAtKStride + 8 * (t + 1));
         }
         if (t < 3) {
 #pragma unroll
-            for (int grp = 3 * t; grp < (t == 2 ? 8 : 3 * t + 3); ++grp) {   // group = 4 consecutive keys: (sub, g)
-                const int sub = grp >> 2, g = grp & 3;
-                const float4 mk = *reinterpret_cast<const float4*>(Ms + sub * 32 + 8 * g + 4 * hi);
-                sc[sub][4 * g + 0] += mk.x;
-                sc[sub][4 * g + 1] += mk.y;
-                sc[sub][4 * g + 2] += mk.z;
-                sc[sub][4 * g + 3] += mk.w;
-                mx = __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fmaxf(sc[sub][4 * g], sc[sub][4 * g + 1]),
-                                                         __builtin_fmaxf(sc[sub][4 * g + 2], sc[sub][4 * g + 3])));
+            for (int j = 0; j < 3; ++j) {
+                const int grp = 3 * t + j;
+                if (grp < 8) mk_next[j] = *reinterpret_cast<const float4*>(mrow + (grp >> 2) * 32 + 8 * (grp & 3));
             }
-            if (t == 2) mx_other = __shfl_xor(mx, 32, 64);
-        } else {
+        }
+        if (kMore) {
+            if (t == 0) sg.fetch_v01(st + 1);
+            if (t == 1) sg.fetch_v23(st + 1);
+            if (t == 2) sg.fetch_k01(nk);
+            if (t == 3) sg.fetch_k23(nk);
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+                sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[sub].x, q[4 * t + 0], sn[sub], 0, 0, 0);
+                sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[sub].y, q[4 * t + 1], sn[sub], 0, 0, 0);
+                sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[sub].z, q[4 * t + 2], sn[sub], 0, 0, 0);
+                sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[sub].w, q[4 * t + 3], sn[sub], 0, 0, 0);
+            }
+        }
+        if (t >= 1 && t <= 3) {
+#pragma unroll
+            for (int j = 0; j < 3; ++j) {
+                const int grp = 3 * (t - 1) + j;
+                if (grp < 8) {
+                    const int sub = grp >> 2, g = grp & 3;
+                    sc[sub][4 * g + 0] += mk[j].x;
+                    sc[sub][4 * g + 1] += mk[j].y;
+                    sc[sub][4 * g + 2] += mk[j].z;
+                    sc[sub][4 * g + 3] += mk[j].w;
+                    mx = __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fmaxf(sc[sub][4 * g], sc[sub][4 * g + 1]),
+                                                             __builtin_fmaxf(sc[sub][4 * g + 2], sc[sub][4 * g + 3])));
+                }
+            }
             if (t == 3) {
+                // both half-waves hold keys of the same query: swap the halves of two copies and take the maximum.
                 // Key 0 of stage 0 is always inside the sequence, so the maximum is finite from the first stage on.
-                m_new = __builtin_fmaxf(m_run, __builtin_fmaxf(mx, mx_other));
+                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+                m_new = __builtin_fmaxf(m_run, __builtin_fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1])));
                 alpha = __builtin_amdgcn_exp2f(m_run - m_new);
                 m_run = m_new;
             }
+        } else if (t >= 4) {
 #pragma unroll
-            for (int i = exp_end[t - 1]; i < exp_end[t]; ++i) {
+            for (int i = 8 * (t - 4); i < 8 * (t - 4) + 8; ++i) {
                 sc[i >> 4][i & 15] = __builtin_amdgcn_exp2f(sc[i >> 4][i & 15] - m_new);
                 psum += sc[i >> 4][i & 15];
             }
-            if (t >= 4) {
 #pragma unroll
-                for (int e = 4 * (t - 4); e < 4 * (t - 4) + 4; ++e) {
-                    o[0][e] *= alpha;
-                    o[1][e] *= alpha;
-                }
+            for (int e = 4 * (t - 4); e < 4 * (t - 4) + 4; ++e) {
+                o[0][e] *= alpha;
+                o[1][e] *= alpha;
             }
         }
         if (kMore) {   // issue order within the chunk: the LDS reads, then one MFMA, four vector instructions, one MFMA, ...
@@ -148,27 +238,39 @@ __device__ __forceinline__ void attention_trip(const float* Kn, const float* Vs,
             }
         }
         __builtin_amdgcn_sched_barrier(0);
+        kf[0] = kf_next[0];
+        kf[1] = kf_next[1];
+        mk[0] = mk_next[0];
+        mk[1] = mk_next[1];
+        mk[2] = mk_next[2];
     }
     l_run = l_run * alpha + psum;
-    // O^T += V^T P^T: MFMA (sub, e) pairs key 32 sub + 8 (e/4) + e%4 (lower half-wave) with the key four
-    // further on (upper half-wave) -- the keys whose probabilities the two halves hold in register e.
+    // O^T += V^T P^T: MFMA pair i = (sub, e) joins key 32 sub + 8 (e/4) + e%4 (lower half-wave) with the key four
+    // further on (upper half-wave) -- the keys whose probabilities the two halves hold in register e.  The V
+    // operands of a pair are read kAhead pairs before their MFMAs (explicit ring, fenced so that it stays that
+    // way), and -- kMore -- the tiles fetched above go to LDS one store at a time under the last pairs (their
+    // buffers were last read in the previous trip).
+    constexpr int kAhead = 4;
+    float va[kAhead + 1][2];
+    const float* vcol = Vs + 4 * hi * kAtVStride + lq;
+    auto vkey = [](int i) { return (i >> 4) * 32 + 8 * ((i & 15) >> 2) + (i & 3); };
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const float* vrow = Vs + (sub * 32 + 8 * (e >> 2) + 4 * hi + (e & 3)) * kAtVStride + lq;
-            o[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[0], sc[sub][e], o[0], 0, 0, 0);
-            o[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[32], sc[sub][e], o[1], 0, 0, 0);
-        }
-    // issue order: V operands are read three MFMA pairs ahead of their use, so no MFMA waits for LDS
-    __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
-#pragma unroll
-    for (int i = 0; i < 29; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    for (int i = 0; i < kAhead; ++i) {
+        va[i][0] = vcol[vkey(i) * kAtVStride];
+        va[i][1] = vcol[vkey(i) * kAtVStride + 32];
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
     __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+        if (i + kAhead < 32) {
+            va[(i + kAhead) % (kAhead + 1)][0] = vcol[vkey(i + kAhead) * kAtVStride];
+            va[(i + kAhead) % (kAhead + 1)][1] = vcol[vkey(i + kAhead) * kAtVStride + 32];
+        }
+        o[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(va[i % (kAhead + 1)][0], sc[i >> 4][i & 15], o[0], 0, 0, 0);
+        o[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(va[i % (kAhead + 1)][1], sc[i >> 4][i & 15], o[1], 0, 0, 0);
+        if (kMore && i >= 20 && i < 29) sg.stash_piece(i - 20, st);
+        __builtin_amdgcn_sched_barrier(0);
+    }
 }
 
 __global__ __launch_bounds__(kAtThreads, 2) void attention_mfma_kernel(AttnArgs a)
@@ -190,63 +292,27 @@ __global__ __launch_bounds__(kAtThreads, 2) void attention_mfma_kernel(AttnArgs 
     const float* base = a.qkv + b * S * ld + (int64_t)h * kAtD;   // Q of token 0 of this sequence and head
     const int64_t q0 = (int64_t)qb * kAtQB + wave * kAtQW;
 
-    // Staging: thread t carries chunks t, t + 256, ... of the 64 x 16 float4 chunks of a K and of a V tile
-    // (chunk i: key st_key + 16 i, 16-byte column st_ch).  Offsets within the sequence fit 32 bits (checked
-    // by the launcher).  Fetches and stashes are unconditional -- past the last stage they repeat it into a
-    // tile nobody reads -- so that every trip of the loop is one straight line with all its loads issued at
-    // the top and awaited only at the bottom.
-    float4 k0r, k1r, k2r, k3r, v0r, v1r, v2r, v3r;
-    float mreg = 0.0f;
+    AttnStager sg;
     const int S32 = (int)S, ld32 = (int)ld;
     const int n_stages = (S32 + kAtKB - 1) / kAtKB;
-    const int st_key = tid >> 4, st_ch = tid & 15;
-    const float* const kbase = base + HD;       // K and V of token 0 of this sequence and head (wave-uniform)
-    const float* const vbase = base + 2 * HD;
-    const float* const mrow = a.mask ? a.mask + b * S : nullptr;
-    float* const k_tiles = lds;
-    float* const v_tiles = lds + 2 * kAtKTile;
-    // Offset (in floats, from kbase / vbase) of this thread's chunk i of stage 0, and the offset of the same
-    // column in the last row of the sequence: a stage further on is +64 rows, clamped to that.
-    const unsigned off_last = (unsigned)(S32 - 1) * (unsigned)ld32 + 4u * st_ch;
-    const unsigned off_st0 = (unsigned)st_key * (unsigned)ld32 + 4u * st_ch, off_16 = 16u * (unsigned)ld32;
-    const unsigned off_stage = (unsigned)kAtKB * (unsigned)ld32;
-#define Q8_AT_OFF(stage, i) min(off_st0 + (unsigned)(stage) * off_stage + (unsigned)(i) * off_16, off_last)
-#define Q8_AT_FETCH_K(stage)                                                          \
-    {                                                                                 \
-        k0r = *reinterpret_cast<const float4*>(kbase + Q8_AT_OFF(stage, 0));           \
-        k1r = *reinterpret_cast<const float4*>(kbase + Q8_AT_OFF(stage, 1));           \
-        k2r = *reinterpret_cast<const float4*>(kbase + Q8_AT_OFF(stage, 2));           \
-        k3r = *reinterpret_cast<const float4*>(kbase + Q8_AT_OFF(stage, 3));           \
-    }
-#define Q8_AT_FETCH_V(stage)                                                          \
-    {                                                                                 \
-        v0r = *reinterpret_cast<const float4*>(vbase + Q8_AT_OFF(stage, 0));           \
-        v1r = *reinterpret_cast<const float4*>(vbase + Q8_AT_OFF(stage, 1));           \
-        v2r = *reinterpret_cast<const float4*>(vbase + Q8_AT_OFF(stage, 2));           \
-        v3r = *reinterpret_cast<const float4*>(vbase + Q8_AT_OFF(stage, 3));           \
-        if (mrow) mreg = mrow[min((stage) * kAtKB + (tid & 63), S32 - 1)];             \
-    }
-#define Q8_AT_STASH_K(buf)                                                            \
-    {                                                                                 \
-        float* w = k_tiles + (buf) * kAtKTile + st_key * kAtKStride + 4 * st_ch;      \
-        *reinterpret_cast<float4*>(w) = k0r;                                          \
-        *reinterpret_cast<float4*>(w + 16 * kAtKStride) = k1r;                        \
-        *reinterpret_cast<float4*>(w + 32 * kAtKStride) = k2r;                        \
-        *reinterpret_cast<float4*>(w + 48 * kAtKStride) = k3r;                        \
-    }
-    // the mask row goes in with the V tile, in log2 units; beyond the sequence -inf: weight 0 whatever the
-    // (repeated) row holds
-#define Q8_AT_STASH_V(buf, stage)                                                     \
-    {                                                                                 \
-        float* w = v_tiles + (buf) * kAtVTile + st_key * kAtVStride + 4 * st_ch;      \
-        *reinterpret_cast<float4*>(w) = v0r;                                          \
-        *reinterpret_cast<float4*>(w + 16 * kAtVStride) = v1r;                        \
-        *reinterpret_cast<float4*>(w + 32 * kAtVStride) = v2r;                        \
-        *reinterpret_cast<float4*>(w + 48 * kAtVStride) = v3r;                        \
-        if (tid < kAtKB)                                                              \
-            v_tiles[(buf) * kAtVTile + kAtKB * kAtVStride + tid] =                    \
-                ((stage) * kAtKB + tid < S32) ? mreg * 1.44269504088896341f : -__builtin_inff(); \
-    }
+    sg.S32 = S32;
+    sg.tid = tid;
+    sg.st_key = tid >> 4;
+    sg.st_ch = tid & 15;
+    sg.kbase = base + HD;
+    sg.vbase = base + 2 * HD;
+    sg.mrow = a.mask ? a.mask + b * S : nullptr;
+    sg.k_tiles = lds;
+    sg.v_tiles = lds + 2 * kAtKTile;
+    // offset (in floats, from kbase / vbase) of this thread's chunk 0 of stage 0, the steps to the next chunk and
+    // the next stage, and the offset of the same column in the last row of the sequence
+    sg.off_st0 = (unsigned)sg.st_key * (unsigned)ld32 + 4u * sg.st_ch;
+    sg.off_16 = 16u * (unsigned)ld32;
+    sg.off_stage = (unsigned)kAtKB * (unsigned)ld32;
+    sg.off_last = (unsigned)(S32 - 1) * (unsigned)ld32 + 4u * sg.st_ch;
+    sg.m = 0.0f;
+    float* const k_tiles = sg.k_tiles;
+    float* const v_tiles = sg.v_tiles;
 
     v16f o[2];           // O^T: o[blk][e] = ctx[query lq][column 32 blk + 8 (e/4) + 4 hi + e%4], not yet normalised
 #pragma unroll
@@ -259,7 +325,8 @@ __global__ __launch_bounds__(kAtThreads, 2) void attention_mfma_kernel(AttnArgs 
     // of V in LDS, and two ahead in the staging registers.
     v16f s_cur[2], s_nxt[2];
     const int last = n_stages - 1;
-    Q8_AT_FETCH_K(0)
+    sg.fetch_k01(0);
+    sg.fetch_k23(0);
     // The wave's queries, requested behind the first K tile so that the two latencies overlap: lane (lq, hi)
     // holds, for t = 0..7, columns 8t + 4hi .. 8t + 4hi + 3 of query lq, times scale * log2 e.  A row beyond
     // the sequence repeats the last one (computed, never stored).
@@ -271,9 +338,11 @@ __global__ __launch_bounds__(kAtThreads, 2) void attention_mfma_kernel(AttnArgs 
 #pragma unroll
         for (int t = 0; t < 8; ++t) qraw[t] = qp[2 * t];
     }
-    Q8_AT_STASH_K(0)
-    Q8_AT_FETCH_V(0)
-    Q8_AT_FETCH_K(min(1, last))
+    sg.stash_k(0);
+    sg.fetch_v01(0);
+    sg.fetch_v23(0);
+    sg.fetch_k01(min(1, last));
+    sg.fetch_k23(min(1, last));
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
         q[4 * t + 0] = qraw[t].x * a.c;
@@ -283,26 +352,22 @@ __global__ __launch_bounds__(kAtThreads, 2) void attention_mfma_kernel(AttnArgs 
     }
     __syncthreads();
     attention_scores(k_tiles, q, lq, hi, s_cur);
-    Q8_AT_STASH_V(0, 0)
-    Q8_AT_STASH_K(1)
+    sg.stash_v(0, 0);
+    sg.stash_k(1);
     __syncthreads();
 
     for (int st = 0; st < n_stages; ++st) {
-        const bool more = st < last;
-        const int nv = min(st + 1, last), nk = min(st + 2, last);
-        Q8_AT_FETCH_V(nv)
-        Q8_AT_FETCH_K(nk)
         const float* Vs = v_tiles + (st & 1) * kAtVTile;
         const float* Ms = Vs + kAtKB * kAtVStride;
-        if (more)
-            attention_trip<true>(k_tiles + ((st + 1) & 1) * kAtKTile, Vs, Ms, q, lq, hi, s_cur, s_nxt, o, m_run, l_run);
-        else
-            attention_trip<false>(k_tiles, Vs, Ms, q, lq, hi, s_cur, s_nxt, o, m_run, l_run);
-        Q8_AT_STASH_V((st + 1) & 1, nv)
-        Q8_AT_STASH_K(st & 1)
-        __syncthreads();
-        s_cur[0] = s_nxt[0];
-        s_cur[1] = s_nxt[1];
+        if (st < last) {
+            attention_trip<true>(k_tiles + ((st + 1) & 1) * kAtKTile, Vs, Ms, q, lq, hi, s_cur, s_nxt, o, m_run, l_run, sg, st,
+                                 min(st + 2, last));
+            __syncthreads();
+            s_cur[0] = s_nxt[0];
+            s_cur[1] = s_nxt[1];
+        } else {
+            attention_trip<false>(k_tiles, Vs, Ms, q, lq, hi, s_cur, s_nxt, o, m_run, l_run, sg, st, last);
+        }
     }
 
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -401,12 +466,6 @@ __global__ __launch_bounds__(64) void attention_generic_kernel(const float* __re
         if (lane == 0 && m) atomicMax(slots + (blockIdx.x % kAtSlots), m);
     }
 }
-
-#undef Q8_AT_OFF
-#undef Q8_AT_FETCH_K
-#undef Q8_AT_FETCH_V
-#undef Q8_AT_STASH_K
-#undef Q8_AT_STASH_V
 
 __global__ void attention_slots_clear_kernel(unsigned* slots)
 {
