@@ -154,17 +154,16 @@ __device__ __forceinline__ void attention_trip(const float* Kn, const float* Vs,
                                                int hi, v16f (&sc)[2], v16f (&sn)[2], v16f (&o)[2], float& m_run, float& l_run,
                                                AttnStager& sg, int st, int nk)
 {
+    v16f zero;   // C operand of the first MFMA of a chain (becomes the instruction's inline constant: nothing to clear)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) zero[e] = 0.0f;
     float mx = -__builtin_inff(), m_new = 0.0f, alpha = 1.0f, psum = 0.0f;
     const float* krow = Kn + lq * kAtKStride + 4 * hi;     // sub-block 1 is 32 rows further on
     const float* mrow = Ms + 4 * hi;
     float4 kf[2], kf_next[2], mk[3], mk_next[3];
     if (kMore) {
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) sn[sub][e] = 0.0f;
-            kf[sub] = *reinterpret_cast<const float4*>(krow + sub * 32 * kAtKStride);
-        }
+        for (int sub = 0; sub < 2; ++sub) kf[sub] = *reinterpret_cast<const float4*>(krow + sub * 32 * kAtKStride);
     }
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
@@ -189,7 +188,7 @@ __device__ __forceinline__ void attention_trip(const float* Kn, const float* Vs,
             if (t == 3) sg.fetch_k23(nk);
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub) {
-                sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[sub].x, q[4 * t + 0], sn[sub], 0, 0, 0);
+                sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[sub].x, q[4 * t + 0], t == 0 ? zero : sn[sub], 0, 0, 0);
                 sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[sub].y, q[4 * t + 1], sn[sub], 0, 0, 0);
                 sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[sub].z, q[4 * t + 2], sn[sub], 0, 0, 0);
                 sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[sub].w, q[4 * t + 3], sn[sub], 0, 0, 0);
