@@ -242,8 +242,11 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 static int ln_grid(int64_t M)
 {
-    int64_t g = (M + kLnThreads / 64 - 1) / (kLnThreads / 64);
-    return (int)(g < 1 ? 1 : (g < kLnSlots ? g : kLnSlots));
+    // one slot per workgroup caps the grid; within the cap, spread the rows evenly over the trips
+    const int64_t need = (M + kLnThreads / 64 - 1) / (kLnThreads / 64);
+    if (need <= 1) return 1;
+    const int64_t trips = (need + kLnSlots - 1) / kLnSlots;
+    return (int)((need + trips - 1) / trips);
 }
 
 int launch_layernorm(const float* a, const float* r, const float* gamma, const float* beta, float eps, int64_t M,
