@@ -237,25 +237,20 @@ class Layer:
             self.slots_c = self.torch.zeros(q8.AMAX_SLOTS, device="cuda")
             self.slots_o = self.torch.zeros(q8.AMAX_SLOTS, device="cuda")
             self.ctx_l = self.torch.empty((M, H), device="cuda")
-        sx = self.scal[1:2]
-        xq = self.xq[: M * H].view(M, H)
-        q8.q8_quantize_amax(self.x_in, self.slots_x, sx, xq)
-        q8.q8_linear(xq, self.w_qkv, self.b_qkv, sx, self.s_qkv, self.qkv, n_groups=3)
+        sc = self.scal[0:2]                                          # max|x| and S_x of the current FC
+        xq = self.xq[: M * H]
+        q8.q8_linear_f32_slots(self.x_in, self.slots_x, self.w_qkv, self.b_qkv, self.s_qkv, xq, sc, self.qkv, n_groups=3)
         if ev is not None:
             ev[0].record()
         q8.q8_attention(self.qkv, self.batch, self.seq, self.heads, H // self.heads, ctx=self.ctx_l, amax_slots=self.slots_c)
         if ev is not None:
             ev[1].record()
-        q8.q8_quantize_amax(self.ctx_l, self.slots_c, sx, xq)
-        q8.q8_linear(xq, self.w_o, self.b_o, sx, self.s_o, self.attn_out)
+        q8.q8_linear_f32_slots(self.ctx_l, self.slots_c, self.w_o, self.b_o, self.s_o, xq, sc, self.attn_out)
         q8.q8_layernorm_absmax(self.x_in, self.ln_g, self.ln_b, self.h1f, residual=self.attn_out, amax_slots=self.slots_h)
-        g_amax, g_scale = self.gscal[0:1], self.gscal[1:2]
-        g_amax.zero_()
-        q8.q8_quantize_amax(self.h1f, self.slots_h, sx, xq)
-        q8.q8_linear(xq, self.w_1, self.b_1, sx, self.s_1, self.g, out_amax=g_amax, flags=q8.EPI_GELU | q8.EPI_ABSMAX)
-        xq2 = self.xq[: M * F].view(M, F)
-        q8.q8_quantize_amax(self.g, g_amax, g_scale, xq2)
-        q8.q8_linear(xq2, self.w_2, self.b_2, g_scale, self.s_2, self.out)
+        g_amax = self.gscal[0:1]                                      # reset by the call whose epilogue fills it
+        q8.q8_linear_f32_slots(self.h1f, self.slots_h, self.w_1, self.b_1, self.s_1, xq, sc, self.g, out_amax=g_amax,
+                               flags=q8.EPI_GELU | q8.EPI_ABSMAX)
+        q8.q8_linear_f32_slots(self.g, g_amax, self.w_2, self.b_2, self.s_2, self.xq[: M * F], sc, self.out)
         q8.q8_layernorm_absmax(self.h1f, self.ln_g, self.ln_b, self.x_next, residual=self.out, amax_slots=self.slots_o)
 
     def step_layer_static(self):

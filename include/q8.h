@@ -137,6 +137,24 @@ q8_status q8_linear_f32(const float* x, const int8_t* wq, const float* bias,
                         uint32_t epilogue_flags, void* stream);
 
 /*
+ * The same layer when the producer of x has already left the abs-max of x behind
+ * (q8_layernorm_absmax, q8_embedding_sum3_layernorm, q8_attention, or the Q8_EPI_ABSMAX
+ * epilogue of the previous layer): S_x = 127 / max(amax_slots[0 .. n_slots)) (Eq. 3 on
+ * the maximum of Section 4.1), quantize, q8_linear -- two launches and no pass over x for
+ * its maximum.  Same results as q8_quantize_amax followed by q8_linear.
+ *   amax_slots fp32[n_slots], n_slots >= 1, non-negative values whose maximum is max|x|.
+ *   scal_work fp32[2]: on return scal_work[0] = max|x|, scal_work[1] = S_x.
+ *   Other arguments, and the handling of out_amax, as q8_linear_f32.
+ */
+q8_status q8_linear_f32_slots(const float* x, const float* amax_slots, int n_slots,
+                              const int8_t* wq, const float* bias,
+                              const float* sw, int n_groups,
+                              int64_t M, int64_t N, int64_t K,
+                              int8_t* xq_work, float* scal_work,
+                              void* y, int32_t* acc_out, float* out_amax, const float* next_scale,
+                              uint32_t epilogue_flags, void* stream);
+
+/*
  * The quantized Embedding layer at inference (Section 3): returns the Int8 rows,
  * or the rows divided by the table's scale for the FP32 sum + LayerNorm that follow.
  *   table int8[V,H]; scale fp32[1] (ignored when out_is_int8); ids int32[T].

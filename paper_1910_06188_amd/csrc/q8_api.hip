@@ -121,6 +121,30 @@ q8_status q8_linear_f32(const float* x, const int8_t* wq, const float* bias, con
                      stream);
 }
 
+q8_status q8_linear_f32_slots(const float* x, const float* amax_slots, int n_slots, const int8_t* wq, const float* bias,
+                              const float* sw, int n_groups, int64_t M, int64_t N, int64_t K, int8_t* xq_work,
+                              float* scal_work, void* y, int32_t* acc_out, float* out_amax, const float* next_scale,
+                              uint32_t flags, void* stream)
+{
+    if (!scal_work || !amax_slots) return Q8_ERR_NULL;
+    if (n_slots < 1) return Q8_ERR_SHAPE;
+    if (misaligned(scal_work, 4) || misaligned(amax_slots, 4)) return Q8_ERR_ALIGN;
+    q8_status s = check_linear(xq_work, wq, bias, scal_work + 1, sw, n_groups, M, N, K, y, acc_out, out_amax,
+                               next_scale, flags);
+    if (s != Q8_OK) return s;
+    if (M > 0 && K > 0 && (!x || !xq_work)) return Q8_ERR_NULL;
+    if (misaligned(x, 4)) return Q8_ERR_ALIGN;
+    if (M * K == 0) {
+        if (q8::launch_absmax(x, 0, scal_work, scal_work + 1, as_stream(stream))) return Q8_ERR_LAUNCH;
+        if ((flags & Q8_EPI_ABSMAX) && q8::launch_absmax(x, 0, out_amax, nullptr, as_stream(stream))) return Q8_ERR_LAUNCH;
+    } else if (q8::launch_quantize_amax(x, M * K, amax_slots, n_slots, scal_work, scal_work + 1, xq_work,
+                                        (flags & Q8_EPI_ABSMAX) ? out_amax : nullptr, as_stream(stream))) {
+        return Q8_ERR_LAUNCH;
+    }
+    return q8_linear(xq_work, wq, bias, scal_work + 1, sw, n_groups, M, N, K, y, acc_out, out_amax, next_scale, flags,
+                     stream);
+}
+
 q8_status q8_embedding(const int8_t* table, const float* scale, int64_t V, int64_t H, const int32_t* ids, int64_t T,
                        void* out, int out_is_int8, int32_t* err_flag, void* stream)
 {

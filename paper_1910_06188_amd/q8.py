@@ -47,7 +47,8 @@ _lib.q8_layernorm_absmax.argtypes = [_vp, _vp, _vp, _vp, _f32, _i64, _i64, _vp, 
 _lib.q8_embedding_sum3_layernorm.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _f32,
                                              _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.q8_attention.argtypes = [_vp, _i64, _i64, _i32, _i32, _vp, _f32, _vp, _vp, _vp, _vp, _vp]
-for _f in ("q8_attention", "q8_layernorm_absmax", "q8_embedding_sum3_layernorm", "q8_fake_quantize", "q8_ema_update", "q8_fake_quantize_ema", "q8_ste_backward", "q8_absmax", "q8_scale_from_amax", "q8_quantize", "q8_quantize_amax", "q8_linear", "q8_linear_f32", "q8_embedding",
+_lib.q8_linear_f32_slots.argtypes = [_vp, _vp, _i32, _vp, _vp, _vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _u32, _vp]
+for _f in ("q8_linear_f32_slots", "q8_attention", "q8_layernorm_absmax", "q8_embedding_sum3_layernorm", "q8_fake_quantize", "q8_ema_update", "q8_fake_quantize_ema", "q8_ste_backward", "q8_absmax", "q8_scale_from_amax", "q8_quantize", "q8_quantize_amax", "q8_linear", "q8_linear_f32", "q8_embedding",
            "q8_embedding_sum3"):
     getattr(_lib, _f).restype = C.c_int
 _lib.q8_version.restype = C.c_char_p
@@ -144,6 +145,20 @@ def q8_linear_f32(x, wq, bias, sw, xq_work, scal_work, y, n_groups=1, acc_out=No
     _ck(_lib.q8_linear_f32(_ptr(x), _ptr(wq), _ptr(bias), _ptr(sw), n_groups, M, N, K, _ptr(xq_work),
                            _ptr(scal_work), _ptr(y), _ptr(acc_out), _ptr(out_amax), _ptr(next_scale), flags,
                            _stream(stream)), "q8_linear_f32")
+
+
+def q8_linear_f32_slots(x, amax_slots, wq, bias, sw, xq_work, scal_work, y, n_groups=1, acc_out=None, out_amax=None,
+                        next_scale=None, flags=0, stream=None) -> None:
+    """Dynamic-quantization FC layer fed by abs-max slots its producer left: quantize (scale from the slots), GEMM."""
+    M, K = x.shape
+    N, K2 = wq.shape
+    if K != K2 or y.numel() != M * N or xq_work.numel() < M * K or scal_work.numel() < 2 or amax_slots.numel() < 1:
+        raise ValueError("q8_linear_f32_slots: shape mismatch")
+    if sw.numel() != n_groups or (bias is not None and bias.numel() != N):
+        raise ValueError("q8_linear_f32_slots: scale/bias size mismatch")
+    _ck(_lib.q8_linear_f32_slots(_ptr(x), _ptr(amax_slots), amax_slots.numel(), _ptr(wq), _ptr(bias), _ptr(sw), n_groups,
+                                 M, N, K, _ptr(xq_work), _ptr(scal_work), _ptr(y), _ptr(acc_out), _ptr(out_amax),
+                                 _ptr(next_scale), flags, _stream(stream)), "q8_linear_f32_slots")
 
 
 def q8_embedding(table, scale, ids, out, err_flag=None, stream=None) -> None:

@@ -101,6 +101,13 @@ def test_host_side_argument_checks(lib):
     assert lib.q8_layernorm_absmax(p + 2, None, p, p, 1e-12, 1, 4, p, None, None, None, None) == ALIGN
     assert lib.q8_embedding_sum3_layernorm(p, 4, p, 4, p, 4, p, 4, None, p, p, 2, p, p, 1e-12, p, None, None, None, None, None) == NULL
     assert lib.q8_embedding_sum3_layernorm(p, 4, p, 4, p, 4, p, 0, p, p, p, 2, p, p, 1e-12, p, None, None, None, None, None) == SHAPE
+    # the FC fed by abs-max slots
+    lib.q8_linear_f32_slots.argtypes = [vp, vp, C.c_int, vp, vp, vp, C.c_int, i64, i64, i64, vp, vp, vp, vp, vp, vp, C.c_uint32, vp]
+    assert lib.q8_linear_f32_slots(p, None, 1, p, None, p, 1, 4, 4, 128, p, p, p, None, None, None, 0, None) == NULL
+    assert lib.q8_linear_f32_slots(p, p, 0, p, None, p, 1, 4, 4, 128, p, p, p, None, None, None, 0, None) == SHAPE
+    assert lib.q8_linear_f32_slots(p, p, 1, p, None, p, 1, 4, 4, 128, p, None, p, None, None, None, 0, None) == NULL
+    assert lib.q8_linear_f32_slots(p, p + 2, 1, p, None, p, 1, 4, 4, 128, p, p, p, None, None, None, 0, None) == ALIGN
+    assert lib.q8_linear_f32_slots(None, p, 1, p, None, p, 1, 4, 4, 128, p, p, p, None, None, None, 0, None) == NULL
     # FP32 attention between the QKV and attention-output FC layers
     lib.q8_attention.argtypes = [vp, i64, i64, C.c_int, C.c_int, vp, C.c_float, vp, vp, vp, vp, vp]
     assert lib.q8_attention(p, -1, 8, 2, 64, None, 0.125, p, None, None, None, None) == SHAPE

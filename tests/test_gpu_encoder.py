@@ -2,7 +2,8 @@
 
 A layer is: quantize (scale from the abs-max slots of the producer) -> fused Q|K|V FC -> FP32 softmax attention ->
 quantize -> attention-output FC -> residual + LayerNorm -> quantize -> FFN1 FC + GELU -> quantize -> FFN2 FC ->
-residual + LayerNorm (Section 3: FC layers quantized, Softmax / LayerNorm / GELU in FP32; Section 4.1: dynamic scales).
+residual + LayerNorm, each quantize + FC pair being one q8_linear_f32_slots call (Section 3: FC layers quantized,
+Softmax / LayerNorm / GELU in FP32; Section 4.1: dynamic scales).
 Each stage is compared with the oracle applied to the input the GPU itself gave that stage, at that stage's own
 bar (int8 codes and scales bit-exact, FC outputs 1e-6 relative, LayerNorm 1e-6 relative, attention 1e-5 of
 max|V|, GELU outputs abs 1e-6 + rel 1e-5): an end-to-end comparison would measure how rounding-boundary flips of
@@ -84,24 +85,21 @@ class Work:
         self.xq_x, self.xq_c, self.xq_h = (torch.empty((M, H), dtype=torch.int8, device="cuda") for _ in range(3))
         self.xq_g = torch.empty((M, F), dtype=torch.int8, device="cuda")
         self.slots_c, self.slots_h = (torch.zeros(q8.AMAX_SLOTS, device="cuda") for _ in range(2))
-        self.sc = torch.zeros(4, device="cuda")       # the four activation scales of the layer
-        self.g_amax = torch.zeros(1, device="cuda")
+        self.sc = torch.zeros(8, device="cuda")       # (max|x|, S_x) of the layer's four FC inputs
+        self.g_amax = torch.full((1,), 1e9, device="cuda")   # stale on purpose: the FFN1 call resets it
 
 
 def gpu_layer(q8, L, w, x_in, slots_x, x_next, slots_next, B, S, mask=None):
+    """Every FC is one q8_linear_f32_slots call: quantize with the scale from its producer's slots, then the GEMM."""
     H, F = L.H, L.F
     sc = w.sc
-    q8.q8_quantize_amax(x_in, slots_x, sc[0:1], w.xq_x)
-    q8.q8_linear(w.xq_x, L.w_qkv, L.b_qkv, sc[0:1], L.s_qkv, w.qkv, n_groups=3)
+    q8.q8_linear_f32_slots(x_in, slots_x, L.w_qkv, L.b_qkv, L.s_qkv, w.xq_x, sc[0:2], w.qkv, n_groups=3)
     q8.q8_attention(w.qkv, B, S, L.heads, H // L.heads, ctx=w.ctx, mask=mask, amax_slots=w.slots_c)
-    q8.q8_quantize_amax(w.ctx, w.slots_c, sc[1:2], w.xq_c)
-    q8.q8_linear(w.xq_c, L.w_o, L.b_o, sc[1:2], L.s_o, w.attn)
+    q8.q8_linear_f32_slots(w.ctx, w.slots_c, L.w_o, L.b_o, L.s_o, w.xq_c, sc[2:4], w.attn)
     q8.q8_layernorm_absmax(x_in, L.gamma[0], L.beta[0], w.h1, residual=w.attn, amax_slots=w.slots_h)
-    q8.q8_quantize_amax(w.h1, w.slots_h, sc[2:3], w.xq_h)
-    w.g_amax.zero_()
-    q8.q8_linear(w.xq_h, L.w_1, L.b_1, sc[2:3], L.s_1, w.g, out_amax=w.g_amax, flags=q8.EPI_GELU | q8.EPI_ABSMAX)
-    q8.q8_quantize_amax(w.g, w.g_amax, sc[3:4], w.xq_g)
-    q8.q8_linear(w.xq_g, L.w_2, L.b_2, sc[3:4], L.s_2, w.out)
+    q8.q8_linear_f32_slots(w.h1, w.slots_h, L.w_1, L.b_1, L.s_1, w.xq_h, sc[4:6], w.g, out_amax=w.g_amax,
+                           flags=q8.EPI_GELU | q8.EPI_ABSMAX)
+    q8.q8_linear_f32_slots(w.g, w.g_amax, L.w_2, L.b_2, L.s_2, w.xq_g, sc[6:8], w.out)
     q8.q8_layernorm_absmax(w.h1, L.gamma[1], L.beta[1], x_next, residual=w.out, amax_slots=slots_next)
 
 
@@ -112,8 +110,8 @@ def check_layer(L, w, x_in, x_next, B, S, mask=None):
     sc = host(w.sc)
     # the four quantizers: scale = 127 / max|input| (Eq. 3), codes by Eq. 1
     for i, (src, codes) in enumerate(((x, w.xq_x), (ctx, w.xq_c), (h1, w.xq_h), (g, w.xq_g))):
-        assert sc[i] == O.scale(O.absmax(src)), f"scale {i}"
-        np.testing.assert_array_equal(host(codes), O.quantize(src, sc[i]), err_msg=f"codes {i}")
+        assert sc[2 * i] == O.absmax(src) and sc[2 * i + 1] == O.scale(O.absmax(src)), f"scale {i}"
+        np.testing.assert_array_equal(host(codes), O.quantize(src, sc[2 * i + 1]), err_msg=f"codes {i}")
     r = O.linear(x, L.w_qkv_h, L.s_qkv_h, L.b_qkv_h, threads=THREADS)
     rel_close(qkv, r["y"], 1e-6, what="fused QKV")
     a = O.attention(qkv, B, S, L.heads, H // L.heads, mask=mask, threads=THREADS)

@@ -551,6 +551,37 @@ def test_linear_f32_one_call_equals_chain(q8):
             assert host(am)[0] == 1e9 or host(am)[0] == 0.0          # nothing computed: slot untouched or cleared
 
 
+def test_linear_f32_slots_equals_chain(q8):
+    """The FC fed by abs-max slots of its producer: same bytes as the oracle's layer on that x, whatever the number of
+    slots, and the abs-max epilogue's slot is reset by the call itself."""
+    d = synth.fc_layer(48, 260, 384, 300)
+    r = run_linear(q8, d["x"], d["W"], d["b"])
+    M, K = d["x"].shape
+    N = d["W"].shape[0]
+    amax = np.abs(d["x"]).max()
+    xq_work = torch.empty(M * K, dtype=torch.int8, device="cuda")
+    for n_slots in (1, 5, q8.AMAX_SLOTS):
+        slots = np.zeros(n_slots, np.float32)
+        slots[n_slots // 2] = amax                      # the maximum anywhere among the slots, the rest smaller
+        if n_slots > 2:
+            slots[0] = amax / 3
+        scal = torch.zeros(2, device="cuda")
+        y = torch.empty((M, N), device="cuda")
+        acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+        am = torch.full((1,), 1e9, device="cuda")
+        q8.q8_linear_f32_slots(dev(d["x"]), dev(slots), dev(r["wq"]), dev(d["b"]), dev(r["sw"]), xq_work, scal, y, acc_out=acc,
+                               out_amax=am, flags=q8.EPI_ABSMAX)
+        np.testing.assert_array_equal(host(acc), r["acc"])
+        np.testing.assert_array_equal(host(y), r["y"])
+        np.testing.assert_array_equal(host(xq_work).reshape(M, K), r["xq"])
+        assert host(scal)[0] == amax and host(scal)[1] == r["sx"] and host(am)[0] == np.abs(r["y"]).max()
+    # argument checks
+    raw = q8.raw()
+    p = xq_work.data_ptr()
+    assert raw.q8_linear_f32_slots(p, None, 1, p, None, p, 1, 4, 4, 128, p, p, p, None, None, None, 0, None) == 1   # no slots
+    assert raw.q8_linear_f32_slots(p, p, 0, p, None, p, 1, 4, 4, 128, p, p, p, None, None, None, 0, None) == 2      # n_slots < 1
+
+
 @pytest.mark.parametrize("n", [1, 7, 1000, 4_194_304, 12_582_912 + 3])
 def test_linear_f32_scales_and_codes_at_size(q8, n):
     """The fused path's slot-based abs-max: scale and codes bit-exact for sizes from one
