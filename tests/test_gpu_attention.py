@@ -93,6 +93,24 @@ def test_attention(q8, B, S, heads, d, with_mask):
     np.testing.assert_array_equal(host(q3), host(q2))
 
 
+def test_attention_random_shapes(q8):
+    """Twenty random small problems: sequence lengths around the stage (64) and workgroup (128) sizes, with masks."""
+    g = synth.rng(555)
+    for case in range(20):
+        B, heads = int(g.integers(1, 4)), int(g.integers(1, 4))
+        S = int(g.choice([1, 2, 31, 63, 64, 65, 100, 127, 128, 129, 191, 192, 193, 255, 257, 300]))
+        HD = heads * 64
+        qkv = synth.activations(g, B * S, 3 * HD) * np.float32(g.uniform(0.3, 2.0))
+        mask = make_mask(g, B, S) if case % 2 else None
+        ref = O.attention(qkv, B, S, heads, 64, mask=mask, threads=8)
+        ctx = torch.full((B * S, HD), 7.0, device="cuda")
+        slots = torch.full((q8.AMAX_SLOTS,), -1.0, device="cuda")
+        q8.q8_attention(dev(qkv), B, S, heads, 64, ctx=ctx, mask=None if mask is None else dev(mask), amax_slots=slots)
+        got = host(ctx)
+        close(got, ref, float(np.abs(qkv[:, 2 * HD:]).max()))
+        assert host(slots).max() == np.abs(got).max(), (case, B, S, heads)
+
+
 def test_attention_sharp_and_flat_softmax(q8):
     """Scores from near-uniform to near-one-hot rows: the running maximum has to move, and to stay put."""
     g = synth.rng(77)
