@@ -52,7 +52,7 @@ def make_mask(g, B, S):
 
 SHAPES = [  # B, S, heads, d
     (1, 1, 1, 64), (2, 7, 3, 64), (1, 64, 1, 64), (1, 65, 2, 64), (2, 128, 2, 64), (1, 129, 1, 64), (3, 200, 2, 64),
-    (2, 384, 4, 64), (1, 513, 1, 64),
+    (2, 384, 4, 64), (1, 513, 1, 64), (1, 2048, 2, 64),
     (2, 9, 3, 5), (1, 70, 2, 32), (1, 33, 2, 128), (2, 130, 1, 80),   # other head widths: the generic kernel
 ]
 
