@@ -14,8 +14,13 @@
 // exchange between the two half-waves, and the probabilities sit exactly where the B operand of
 // O^T += V^T P^T wants them -- no data movement between the two products.  Softmax is the
 // running-maximum form (scores never exist in memory), evaluated with exp2.
-// Work per (sequence, head): 4 S^2 64 flops; bound by the fp32 matrix pipes (157 TFLOP/s), the
-// traffic (qkv read once per query block from L2, ctx written once) is small beside it.
+// The key loop is skewed by one stage (the scores of stage i+1 are formed while the softmax of
+// stage i runs) and its instruction streams are interleaved by hand, because a wave issues in
+// order: see attention_trip.
+// Work per (sequence, head): 4 S^2 64 flops; bound by the fp32 matrix pipes (157 TFLOP/s) plus
+// the vector arithmetic of the softmax, which on this part is paid on top of the MFMA time
+// rather than beside it; the traffic (qkv read once per query block from L2, ctx written once)
+// is small beside both.
 #include "q8_device.h"
 #include "q8_launch.h"
 
