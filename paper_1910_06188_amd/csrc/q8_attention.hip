@@ -39,8 +39,8 @@ constexpr int kAtKB = 64;                  // keys per stage
 // 4 * 72 = 32 (mod 64) puts the halves on disjoint banks.
 constexpr int kAtKStride = 68;
 constexpr int kAtVStride = 72;
-constexpr int kAtKTile = kAtKB * kAtKStride;             // floats of a K tile in LDS
-constexpr int kAtVTile = kAtKB * kAtVStride + kAtKB;     // V tile and the stage's mask row
+constexpr int kAtKTile = kAtKB * kAtKStride + kAtKB;     // floats of a K tile in LDS, the stage's mask row behind it
+constexpr int kAtVTile = kAtKB * kAtVStride;
 constexpr int kAtStageFloats = kAtKTile + kAtVTile;
 constexpr int kAtSlots = 2048;             // abs-max slots (= Q8_AMAX_SLOTS)
 
@@ -60,12 +60,25 @@ struct AttnArgs {
 
 // S^T block of one stage: s[sub][e] of lane (lq, hi) = <K[32 sub + 8 (e/4) + 4 hi + e%4], c Q[lq]>.  MFMA number
 // 4t + i pairs column 8t + i (lower half-wave) with column 8t + 4 + i (upper half-wave) of both operands.
-__device__ __forceinline__ void attention_scores(const float* Ks, const float (&q)[32], int lq, int hi, v16f (&s)[2])
+__device__ __forceinline__ void attention_load_mask(const float* Ks, int hi, v16f (&s)[2])
 {
+    // the accumulators start at the mask row (log2 units, -inf beyond the sequence), so the mask costs no addition
+    const float* mrow = Ks + kAtKB * kAtKStride + 4 * hi;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) s[sub][e] = 0.0f;
+        for (int g = 0; g < 4; ++g) {
+            const float4 mk = *reinterpret_cast<const float4*>(mrow + sub * 32 + 8 * g);
+            s[sub][4 * g + 0] = mk.x;
+            s[sub][4 * g + 1] = mk.y;
+            s[sub][4 * g + 2] = mk.z;
+            s[sub][4 * g + 3] = mk.w;
+        }
+}
+
+__device__ __forceinline__ void attention_scores(const float* Ks, const float (&q)[32], int lq, int hi, v16f (&s)[2])
+{
+    attention_load_mask(Ks, hi, s);
 #pragma unroll
     for (int t = 0; t < 8; ++t)
 #pragma unroll
@@ -96,25 +109,32 @@ struct AttnStager {
     }
     __device__ __forceinline__ static float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
     __device__ __forceinline__ void fetch_k01(int stage) { k0 = ld4(kbase + off(stage, 0)); k1 = ld4(kbase + off(stage, 1)); }
-    __device__ __forceinline__ void fetch_k23(int stage) { k2 = ld4(kbase + off(stage, 2)); k3 = ld4(kbase + off(stage, 3)); }
-    __device__ __forceinline__ void fetch_v01(int stage) { v0 = ld4(vbase + off(stage, 0)); v1 = ld4(vbase + off(stage, 1)); }
-    __device__ __forceinline__ void fetch_v23(int stage)
+    __device__ __forceinline__ void fetch_k23(int stage)
     {
-        v2 = ld4(vbase + off(stage, 2));
-        v3 = ld4(vbase + off(stage, 3));
+        k2 = ld4(kbase + off(stage, 2));
+        k3 = ld4(kbase + off(stage, 3));
         if (mrow) m = mrow[min(stage * kAtKB + (tid & 63), S32 - 1)];
     }
-    __device__ __forceinline__ void stash_k(int buf) const
+    __device__ __forceinline__ void fetch_v01(int stage) { v0 = ld4(vbase + off(stage, 0)); v1 = ld4(vbase + off(stage, 1)); }
+    __device__ __forceinline__ void fetch_v23(int stage) { v2 = ld4(vbase + off(stage, 2)); v3 = ld4(vbase + off(stage, 3)); }
+    // the mask row goes in with the K tile, in log2 units; beyond the sequence -inf: weight 0 whatever the
+    // (repeated) row holds
+    __device__ __forceinline__ float mask_value(int stage) const
+    {
+        return (stage * kAtKB + tid < S32) ? m * 1.44269504088896341f : -__builtin_inff();
+    }
+    __device__ __forceinline__ void stash_k(int buf, int stage) const
     {
         float* w = k_tiles + buf * kAtKTile + st_key * kAtKStride + 4 * st_ch;
         *reinterpret_cast<float4*>(w) = k0;
         *reinterpret_cast<float4*>(w + 16 * kAtKStride) = k1;
         *reinterpret_cast<float4*>(w + 32 * kAtKStride) = k2;
         *reinterpret_cast<float4*>(w + 48 * kAtKStride) = k3;
+        if (tid < kAtKB) k_tiles[buf * kAtKTile + kAtKB * kAtKStride + tid] = mask_value(stage);
     }
     // One LDS store of the stash that follows trip st: pieces 0-3 the V tile of stage st + 1, 4-7 the K tile
-    // fetched during that trip, 8 the mask row of stage st + 1.
-    __device__ __forceinline__ void stash_piece(int j, int st) const
+    // of stage nk fetched during that trip, 8 its mask row.
+    __device__ __forceinline__ void stash_piece(int j, int st, int nk) const
     {
         if (j < 4) {
             const float4 v = j == 0 ? v0 : j == 1 ? v1 : j == 2 ? v2 : v3;
@@ -123,68 +143,51 @@ struct AttnStager {
             const float4 k = j == 4 ? k0 : j == 5 ? k1 : j == 6 ? k2 : k3;
             *reinterpret_cast<float4*>(k_tiles + (st & 1) * kAtKTile + (st_key + 16 * (j - 4)) * kAtKStride + 4 * st_ch) = k;
         } else if (tid < kAtKB) {
-            v_tiles[((st + 1) & 1) * kAtVTile + kAtKB * kAtVStride + tid] =
-                ((st + 1) * kAtKB + tid < S32) ? m * 1.44269504088896341f : -__builtin_inff();
+            k_tiles[(st & 1) * kAtKTile + kAtKB * kAtKStride + tid] = mask_value(nk);
         }
     }
-    // the mask row goes in with the V tile, in log2 units; beyond the sequence -inf: weight 0 whatever the
-    // (repeated) row holds
-    __device__ __forceinline__ void stash_v(int buf, int stage) const
+    __device__ __forceinline__ void stash_v(int buf) const
     {
         float* w = v_tiles + buf * kAtVTile + st_key * kAtVStride + 4 * st_ch;
         *reinterpret_cast<float4*>(w) = v0;
         *reinterpret_cast<float4*>(w + 16 * kAtVStride) = v1;
         *reinterpret_cast<float4*>(w + 32 * kAtVStride) = v2;
         *reinterpret_cast<float4*>(w + 48 * kAtVStride) = v3;
-        if (tid < kAtKB)
-            v_tiles[buf * kAtVTile + kAtKB * kAtVStride + tid] =
-                (stage * kAtKB + tid < S32) ? m * 1.44269504088896341f : -__builtin_inff();
     }
 };
 
 // One trip of the key loop, skewed by a stage: the vector ALU runs the running-maximum softmax of the
-// current stage's scores `sc` (log2 units; mask row Ms) while -- kMore -- the matrix pipe forms the next stage's
-// scores `sn` from the K tile Kn; then O^T += V^T P^T of the current stage.  A wave issues in order, so anything
+// current stage's scores `sc` (log2 units, mask included) while -- kMore -- the matrix pipe forms the next stage's
+// scores `sn` from the K tile Kn, its accumulators starting at that stage's mask row; then O^T += V^T P^T of the current stage.  A wave issues in order, so anything
 // that waits (an LDS read used at once, a block of address arithmetic and loads, arithmetic behind a run of
 // MFMAs) stops its MFMAs as well.  The streams are therefore cut into eight chunks issued in a fixed pattern
 // (scheduling groups): every chunk first requests what the NEXT chunk needs from LDS, then alternates one
 // MFMA with a few vector instructions.
-//   chunks 1-3: add the mask row, row maximum of this lane's 32 scores; exchange between the half-waves
+//   chunks 1-3: row maximum of this lane's 32 scores; exchange between the half-waves
 //   chunk  3  : new running maximum m, shrink factor alpha = 2^(m_old - m) of everything accumulated so far
 //   chunks 4-7: p = 2^(s - m), their sum, and O *= alpha (the P V MFMAs of the previous trip are long done)
 //   chunks 0-3: the tile fetches of the stages ahead (V of stage st + 1, K of stage nk), two loads per chunk:
 //               issued between MFMAs they cost the matrix pipe nothing, issued in a block they stop it
 template <bool kMore>
-__device__ __forceinline__ void attention_trip(const float* Kn, const float* Vs, const float* Ms, const float (&q)[32], int lq,
-                                               int hi, v16f (&sc)[2], v16f (&sn)[2], v16f (&o)[2], float& m_run, float& l_run,
+__device__ __forceinline__ void attention_trip(const float* Kn, const float* Vs, const float (&q)[32], int lq, int hi,
+                                               v16f (&sc)[2], v16f (&sn)[2], v16f (&o)[2], float& m_run, float& l_run,
                                                AttnStager& sg, int st, int nk)
 {
-    v16f zero;   // C operand of the first MFMA of a chain (becomes the instruction's inline constant: nothing to clear)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) zero[e] = 0.0f;
     float mx = -__builtin_inff(), m_new = 0.0f, alpha = 1.0f, psum = 0.0f;
     const float* krow = Kn + lq * kAtKStride + 4 * hi;     // sub-block 1 is 32 rows further on
-    const float* mrow = Ms + 4 * hi;
-    float4 kf[2], kf_next[2], mk[3], mk_next[3];
+    float4 kf[2], kf_next[2];
     if (kMore) {
+        attention_load_mask(Kn, hi, sn);
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) kf[sub] = *reinterpret_cast<const float4*>(krow + sub * 32 * kAtKStride);
     }
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
-        // LDS requests for the next chunk: its K fragments, and the mask values of its key groups
-        // (group = 4 consecutive keys (sub, g); chunk c in 1..3 handles groups 3(c-1) .. min(3c, 8) - 1)
+        // LDS requests for the next chunk: its K fragments
         if (kMore && t < 7) {
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub)
                 kf_next[sub] = *reinterpret_cast<const float4*>(krow + sub * 32 * kAtKStride + 8 * (t + 1));
-        }
-        if (t < 3) {
-#pragma unroll
-            for (int j = 0; j < 3; ++j) {
-                const int grp = 3 * t + j;
-                if (grp < 8) mk_next[j] = *reinterpret_cast<const float4*>(mrow + (grp >> 2) * 32 + 8 * (grp & 3));
-            }
         }
         if (kMore) {
             if (t == 0) sg.fetch_v01(st + 1);
@@ -193,7 +196,7 @@ __device__ __forceinline__ void attention_trip(const float* Kn, const float* Vs,
             if (t == 3) sg.fetch_k23(nk);
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub) {
-                sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[sub].x, q[4 * t + 0], t == 0 ? zero : sn[sub], 0, 0, 0);
+                sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[sub].x, q[4 * t + 0], sn[sub], 0, 0, 0);
                 sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[sub].y, q[4 * t + 1], sn[sub], 0, 0, 0);
                 sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[sub].z, q[4 * t + 2], sn[sub], 0, 0, 0);
                 sn[sub] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[sub].w, q[4 * t + 3], sn[sub], 0, 0, 0);
@@ -204,11 +207,7 @@ __device__ __forceinline__ void attention_trip(const float* Kn, const float* Vs,
             for (int j = 0; j < 3; ++j) {
                 const int grp = 3 * (t - 1) + j;
                 if (grp < 8) {
-                    const int sub = grp >> 2, g = grp & 3;
-                    sc[sub][4 * g + 0] += mk[j].x;
-                    sc[sub][4 * g + 1] += mk[j].y;
-                    sc[sub][4 * g + 2] += mk[j].z;
-                    sc[sub][4 * g + 3] += mk[j].w;
+                    const int sub = grp >> 2, g = grp & 3;   // group = 4 consecutive keys
                     mx = __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fmaxf(sc[sub][4 * g], sc[sub][4 * g + 1]),
                                                              __builtin_fmaxf(sc[sub][4 * g + 2], sc[sub][4 * g + 3])));
                 }
@@ -234,7 +233,7 @@ __device__ __forceinline__ void attention_trip(const float* Kn, const float* Vs,
             }
         }
         if (kMore) {   // issue order within the chunk: the LDS reads, then one MFMA, four vector instructions, one MFMA, ...
-            __builtin_amdgcn_sched_group_barrier(0x100, 5, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -244,9 +243,6 @@ __device__ __forceinline__ void attention_trip(const float* Kn, const float* Vs,
         __builtin_amdgcn_sched_barrier(0);
         kf[0] = kf_next[0];
         kf[1] = kf_next[1];
-        mk[0] = mk_next[0];
-        mk[1] = mk_next[1];
-        mk[2] = mk_next[2];
     }
     l_run = l_run * alpha + psum;
     // O^T += V^T P^T: MFMA pair i = (sub, e) joins key 32 sub + 8 (e/4) + e%4 (lower half-wave) with the key four
@@ -272,14 +268,14 @@ __device__ __forceinline__ void attention_trip(const float* Kn, const float* Vs,
         }
         o[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(va[i % (kAhead + 1)][0], sc[i >> 4][i & 15], o[0], 0, 0, 0);
         o[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(va[i % (kAhead + 1)][1], sc[i >> 4][i & 15], o[1], 0, 0, 0);
-        if (kMore && i >= 20 && i < 29) sg.stash_piece(i - 20, st);
+        if (kMore && i >= 20 && i < 29) sg.stash_piece(i - 20, st, nk);
         __builtin_amdgcn_sched_barrier(0);
     }
 }
 
 __global__ __launch_bounds__(kAtThreads, 2) void attention_mfma_kernel(AttnArgs a)
 {
-    extern __shared__ __align__(16) float lds[];   // K tiles of two stages, then V tiles (+ mask rows) of two stages
+    extern __shared__ __align__(16) float lds[];   // K tiles (+ mask rows) of two stages, then V tiles of two stages
     __shared__ unsigned wave_amax[kAtWaves];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lq = lane & 31, hi = lane >> 5;
@@ -342,7 +338,7 @@ __global__ __launch_bounds__(kAtThreads, 2) void attention_mfma_kernel(AttnArgs 
 #pragma unroll
         for (int t = 0; t < 8; ++t) qraw[t] = qp[2 * t];
     }
-    sg.stash_k(0);
+    sg.stash_k(0, 0);
     sg.fetch_v01(0);
     sg.fetch_v23(0);
     sg.fetch_k01(min(1, last));
@@ -356,21 +352,20 @@ __global__ __launch_bounds__(kAtThreads, 2) void attention_mfma_kernel(AttnArgs 
     }
     __syncthreads();
     attention_scores(k_tiles, q, lq, hi, s_cur);
-    sg.stash_v(0, 0);
-    sg.stash_k(1);
+    sg.stash_v(0);
+    sg.stash_k(1, min(1, last));
     __syncthreads();
 
     for (int st = 0; st < n_stages; ++st) {
         const float* Vs = v_tiles + (st & 1) * kAtVTile;
-        const float* Ms = Vs + kAtKB * kAtVStride;
         if (st < last) {
-            attention_trip<true>(k_tiles + ((st + 1) & 1) * kAtKTile, Vs, Ms, q, lq, hi, s_cur, s_nxt, o, m_run, l_run, sg, st,
+            attention_trip<true>(k_tiles + ((st + 1) & 1) * kAtKTile, Vs, q, lq, hi, s_cur, s_nxt, o, m_run, l_run, sg, st,
                                  min(st + 2, last));
             __syncthreads();
             s_cur[0] = s_nxt[0];
             s_cur[1] = s_nxt[1];
         } else {
-            attention_trip<false>(k_tiles, Vs, Ms, q, lq, hi, s_cur, s_nxt, o, m_run, l_run, sg, st, last);
+            attention_trip<false>(k_tiles, Vs, q, lq, hi, s_cur, s_nxt, o, m_run, l_run, sg, st, last);
         }
     }
 
