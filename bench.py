@@ -42,8 +42,8 @@ FFN2_TRAFFIC_BYTES = 134.5e6
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--seq", type=int, default=384)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -394,7 +394,8 @@ def main():
     # the paper's own inference mode (stored activation scales, Eq. 4), reported beside the headline
     layer.calibrate_static()
     n_static = max(10, args.steps // 4)
-    for _ in range(5):
+    n_warm = max(5, args.warmup // 4)          # the clock settles over the first few dozen launches of a new kernel mix
+    for _ in range(n_warm):
         layer.step_static()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -408,7 +409,7 @@ def main():
                                         "requantize epilogue) straight into FFN2"}
     # the same layer with the FP32 glue around the FCs fused into the library (embedding + LayerNorm, residual +
     # LayerNorm twice; each hands the abs-max of its output to the next quantizer): more work per step, reported beside
-    for _ in range(5):
+    for _ in range(n_warm):
         layer.step_fused()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -420,7 +421,7 @@ def main():
                                    "note": "dynamic scales; adds embedding+LayerNorm and the layer's two residual+LayerNorm "
                                            "passes to the step and drops the abs-max passes of QKV and FFN1 (their abs-max "
                                            "comes out of the LayerNorm kernels)"}
-    for _ in range(5):
+    for _ in range(n_warm):
         layer.step_fused_static()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -433,7 +434,7 @@ def main():
                                                   "write the int8 codes of their output, so QKV and FFN1 have no quantize pass"}
     # the whole encoder layer, FP32 softmax attention included (fp32 matrix pipes: 4 S^2 d flops per head), every
     # operation in the library -- the layer-level tokens/s; the attention kernel is timed with events inside the step
-    for _ in range(5):
+    for _ in range(n_warm):
         layer.step_layer()
     torch.cuda.synchronize()
     aev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_static)]
@@ -450,7 +451,7 @@ def main():
                                                "frac_of_fp32_mfma_peak": round(attn_flops / (attn_ms * 1e-3) / 1e12 / FP32_PEAK_TFLOPS, 4)},
                                  "note": "dynamic scales; QKV FC, FP32 softmax attention, attention-output FC, residual + "
                                          "LayerNorm, FFN1 + GELU, FFN2, residual + LayerNorm; no embedding block"}
-    for _ in range(5):
+    for _ in range(n_warm):
         layer.step_layer_static()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
