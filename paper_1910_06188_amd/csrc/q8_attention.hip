@@ -356,18 +356,14 @@ __global__ __launch_bounds__(kAtThreads, 2) void attention_mfma_kernel(AttnArgs 
     sg.stash_k(1, min(1, last));
     __syncthreads();
 
-    for (int st = 0; st < n_stages; ++st) {
-        const float* Vs = v_tiles + (st & 1) * kAtVTile;
-        if (st < last) {
-            attention_trip<true>(k_tiles + ((st + 1) & 1) * kAtKTile, Vs, q, lq, hi, s_cur, s_nxt, o, m_run, l_run, sg, st,
-                                 min(st + 2, last));
-            __syncthreads();
-            s_cur[0] = s_nxt[0];
-            s_cur[1] = s_nxt[1];
-        } else {
-            attention_trip<false>(k_tiles, Vs, q, lq, hi, s_cur, s_nxt, o, m_run, l_run, sg, st, last);
-        }
+    for (int st = 0; st < last; ++st) {
+        attention_trip<true>(k_tiles + ((st + 1) & 1) * kAtKTile, v_tiles + (st & 1) * kAtVTile, q, lq, hi, s_cur, s_nxt, o, m_run,
+                             l_run, sg, st, min(st + 2, last));
+        __syncthreads();
+        s_cur[0] = s_nxt[0];
+        s_cur[1] = s_nxt[1];
     }
+    attention_trip<false>(k_tiles, v_tiles + (last & 1) * kAtVTile, q, lq, hi, s_cur, s_nxt, o, m_run, l_run, sg, last, last);
 
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     const float inv = 1.0f / l_tot;
