@@ -58,11 +58,10 @@ struct AttnArgs {
     float c;              // scale * log2(e)
 };
 
-// S^T block of one stage: s[sub][e] of lane (lq, hi) = <K[32 sub + 8 (e/4) + 4 hi + e%4], c Q[lq]>.  MFMA number
-// 4t + i pairs column 8t + i (lower half-wave) with column 8t + 4 + i (upper half-wave) of both operands.
+// The score accumulators of a stage start at its mask row (log2 units, -inf beyond the sequence; it sits behind
+// the K tile), so the mask costs no addition: s[sub][e] of lane (lq, hi) belongs to key 32 sub + 8 (e/4) + 4 hi + e%4.
 __device__ __forceinline__ void attention_load_mask(const float* Ks, int hi, v16f (&s)[2])
 {
-    // the accumulators start at the mask row (log2 units, -inf beyond the sequence), so the mask costs no addition
     const float* mrow = Ks + kAtKB * kAtKStride + 4 * hi;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
@@ -76,6 +75,9 @@ __device__ __forceinline__ void attention_load_mask(const float* Ks, int hi, v16
         }
 }
 
+// S^T block of one stage (the prologue's; the trips form theirs chunk by chunk): s[sub][e] of lane (lq, hi) =
+// mask + <K[32 sub + 8 (e/4) + 4 hi + e%4], c Q[lq]>.  MFMA number 4t + i pairs column 8t + i (lower half-wave)
+// with column 8t + 4 + i (upper half-wave) of both operands.
 __device__ __forceinline__ void attention_scores(const float* Ks, const float (&q)[32], int lq, int hi, v16f (&s)[2])
 {
     attention_load_mask(Ks, hi, s);
@@ -97,7 +99,7 @@ __device__ __forceinline__ void attention_scores(const float* Ks, const float (&
 struct AttnStager {
     const float *kbase, *vbase;   // K and V of token 0 of this sequence and head (wave-uniform)
     const float* mrow;            // mask row of the sequence, or null
-    float *k_tiles, *v_tiles;     // two K tiles; two (V tile + mask row)
+    float *k_tiles, *v_tiles;     // two (K tile + mask row); two V tiles
     unsigned off_st0, off_16, off_stage, off_last;
     int S32, tid, st_key, st_ch;
     float4 k0, k1, k2, k3, v0, v1, v2, v3;
