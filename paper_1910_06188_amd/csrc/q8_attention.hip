@@ -166,8 +166,8 @@ struct AttnStager {
 // (scheduling groups): every chunk first requests what the NEXT chunk needs from LDS, then alternates one
 // MFMA with a few vector instructions.
 //   chunks 1-3: row maximum of this lane's 32 scores; exchange between the half-waves
-//   chunk  3  : new running maximum m, shrink factor alpha = 2^(m_old - m) of everything accumulated so far
-//   chunks 4-7: p = 2^(s - m), their sum, and O *= alpha (the P V MFMAs of the previous trip are long done)
+//   chunk  3  : reference maximum m; if it has to move, everything accumulated so far shrinks by 2^(m_old - m)
+//   chunks 4-7: p = 2^(s - m) and their sum
 //   chunks 0-3: the tile fetches of the stages ahead (V of stage st + 1, K of stage nk), two loads per chunk:
 //               issued between MFMAs they cost the matrix pipe nothing, issued in a block they stop it
 template <bool kMore>
@@ -175,7 +175,7 @@ __device__ __forceinline__ void attention_trip(const float* Kn, const float* Vs,
                                                v16f (&sc)[2], v16f (&sn)[2], v16f (&o)[2], float& m_run, float& l_run,
                                                AttnStager& sg, int st, int nk)
 {
-    float mx = -__builtin_inff(), m_new = 0.0f, alpha = 1.0f, psum = 0.0f;
+    float mx = -__builtin_inff(), m_new = 0.0f, psum = 0.0f;
     const float* krow = Kn + lq * kAtKStride + 4 * hi;     // sub-block 1 is 32 rows further on
     float4 kf[2], kf_next[2];
     if (kMore) {
@@ -218,20 +218,29 @@ __device__ __forceinline__ void attention_trip(const float* Kn, const float* Vs,
                 // both half-waves hold keys of the same query: swap the halves of two copies and take the maximum.
                 // Key 0 of stage 0 is always inside the sequence, so the maximum is finite from the first stage on.
                 const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-                m_new = __builtin_fmaxf(m_run, __builtin_fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1])));
-                alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-                m_run = m_new;
+                const float row_max = __builtin_fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+                // The reference maximum moves only when some row of the wave outgrows it by more than 2^8: below
+                // that the probabilities are merely up to 256 times larger (harmless in binary32, and the final
+                // division takes it out again), and the 32 multiplications that shrink O are saved.  The first
+                // stage always moves it (the reference starts at -inf).
+                if (__builtin_amdgcn_ballot_w64(row_max > m_run + 8.0f) != 0) {
+                    const float m_up = __builtin_fmaxf(m_run, row_max);
+                    const float alpha = __builtin_amdgcn_exp2f(m_run - m_up);
+                    m_run = m_up;
+                    l_run *= alpha;
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        o[0][e] *= alpha;
+                        o[1][e] *= alpha;
+                    }
+                }
+                m_new = m_run;
             }
         } else if (t >= 4) {
 #pragma unroll
             for (int i = 8 * (t - 4); i < 8 * (t - 4) + 8; ++i) {
                 sc[i >> 4][i & 15] = __builtin_amdgcn_exp2f(sc[i >> 4][i & 15] - m_new);
                 psum += sc[i >> 4][i & 15];
-            }
-#pragma unroll
-            for (int e = 4 * (t - 4); e < 4 * (t - 4) + 4; ++e) {
-                o[0][e] *= alpha;
-                o[1][e] *= alpha;
             }
         }
         if (kMore) {   // issue order within the chunk: the LDS reads, then one MFMA, four vector instructions, one MFMA, ...
@@ -246,7 +255,7 @@ __device__ __forceinline__ void attention_trip(const float* Kn, const float* Vs,
         kf[0] = kf_next[0];
         kf[1] = kf_next[1];
     }
-    l_run = l_run * alpha + psum;
+    l_run += psum;
     // O^T += V^T P^T: MFMA pair i = (sub, e) joins key 32 sub + 8 (e/4) + e%4 (lower half-wave) with the key four
     // further on (upper half-wave) -- the keys whose probabilities the two halves hold in register e.  The V
     // operands of a pair are read kAhead pairs before their MFMAs (explicit ring, fenced so that it stays that
