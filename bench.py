@@ -183,22 +183,19 @@ class Layer:
             # abs-max slots of the layer input, as the previous layer's last LayerNorm would have left them
             q8.q8_layernorm_absmax(self.x, self.ln_g, self.ln_b, self.x_next, amax_slots=self.slots_x)
             self.x_in = self.x_next.clone()
-        sx = self.scal[1:2]
+        sc = self.scal[0:2]
         q8.q8_embedding_sum3_layernorm(self.tables[0], self.tables[1], self.tables[2], self.table_scales, self.ids[0],
                                        self.ids[1], self.ids[2], self.ln_g, self.ln_b, self.emb, amax_slots=self.slots_e,
                                        err_flag=self.err)
-        xq = self.xq[: M * H].view(M, H)
-        q8.q8_quantize_amax(self.x_in, self.slots_x, sx, xq)                       # QKV: slots from the LayerNorm
-        q8.q8_linear(xq, self.w_qkv, self.b_qkv, sx, self.s_qkv, self.qkv, n_groups=3)
+        xq = self.xq[: M * H]
+        # QKV: slots from the LayerNorm
+        q8.q8_linear_f32_slots(self.x_in, self.slots_x, self.w_qkv, self.b_qkv, self.s_qkv, xq, sc, self.qkv, n_groups=3)
         self._fc_dyn(self.ctx, H, self.w_o, self.s_o, self.b_o, self.attn_out)      # attention output: no LayerNorm in front
         q8.q8_layernorm_absmax(self.x_in, self.ln_g, self.ln_b, self.h1f, residual=self.attn_out, amax_slots=self.slots_h)
-        g_amax, g_scale = self.gscal[0:1], self.gscal[1:2]
-        g_amax.zero_()
-        q8.q8_quantize_amax(self.h1f, self.slots_h, sx, xq)                          # FFN1: slots from the LayerNorm
-        q8.q8_linear(xq, self.w_1, self.b_1, sx, self.s_1, self.g, out_amax=g_amax, flags=q8.EPI_GELU | q8.EPI_ABSMAX)
-        xq2 = self.xq[: M * F].view(M, F)
-        q8.q8_quantize_amax(self.g, g_amax, g_scale, xq2)
-        q8.q8_linear(xq2, self.w_2, self.b_2, g_scale, self.s_2, self.out)
+        g_amax = self.gscal[0:1]
+        q8.q8_linear_f32_slots(self.h1f, self.slots_h, self.w_1, self.b_1, self.s_1, xq, sc, self.g, out_amax=g_amax,
+                               flags=q8.EPI_GELU | q8.EPI_ABSMAX)                    # FFN1: slots from the LayerNorm
+        q8.q8_linear_f32_slots(self.g, g_amax, self.w_2, self.b_2, self.s_2, self.xq[: M * F], sc, self.out)
         q8.q8_layernorm_absmax(self.h1f, self.ln_g, self.ln_b, self.x_next, residual=self.out, amax_slots=self.slots_x)
 
     def step_fused_static(self):
