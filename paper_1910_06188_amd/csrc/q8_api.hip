@@ -109,6 +109,11 @@ q8_status q8_linear_f32(const float* x, const int8_t* wq, const float* bias, con
         s = q8_absmax(x, 0, scal_work, scal_work + 1, stream);
         if (s != Q8_OK) return s;
         if ((flags & Q8_EPI_ABSMAX) && q8::launch_absmax(x, 0, out_amax, nullptr, as_stream(stream))) return Q8_ERR_LAUNCH;
+    } else if (M * K <= q8::quantize_onepass_max()) {
+        // a tensor one workgroup can hold in registers: abs-max, scale and quantize in a single launch
+        if (q8::launch_quantize_onepass(x, M * K, scal_work, scal_work + 1, xq_work,
+                                        (flags & Q8_EPI_ABSMAX) ? out_amax : nullptr, as_stream(stream)))
+            return Q8_ERR_LAUNCH;
     } else {
         // abs-max slots in scal_work[2..], folded by the quantize kernel: no atomics, no extra launch
         int slots = 0;

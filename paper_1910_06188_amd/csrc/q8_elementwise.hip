@@ -365,6 +365,50 @@ int launch_absmax_partial(const float* x, int64_t n, float* partials, int* n_par
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
+// Small tensors (latency-bound layers such as a 16-token batch): abs-max, scale and quantize in one launch of one
+// workgroup that keeps its elements in registers between the two steps -- Eq. 3 then Eq. 1, same values as the
+// two-kernel path, one launch less.
+constexpr int kOnePassPerThread = 64;   // 256 threads x 64 = 16384 elements
+constexpr int kOnePassMax = kEwThreads * kOnePassPerThread;
+__global__ __launch_bounds__(kEwThreads) void quantize_onepass_kernel(const float* __restrict__ x, int n, float* amax_out,
+                                                                       float* scale_out, int8_t* __restrict__ q,
+                                                                       float* zero_slot)
+{
+    __shared__ unsigned folded;
+    float v[kOnePassPerThread];
+    unsigned m = 0u;
+#pragma unroll
+    for (int i = 0; i < kOnePassPerThread; ++i) {
+        const int idx = i * kEwThreads + threadIdx.x;
+        v[i] = idx < n ? x[idx] : 0.0f;
+        m = max(m, abs_bits(v[i]));
+    }
+    m = block_max_u32(m);
+    if (threadIdx.x == 0) folded = m;
+    __syncthreads();
+    const float a = __uint_as_float(folded);
+    const float s = scale_from_amax(a);
+    if (threadIdx.x == 0) {
+        amax_out[0] = a;
+        scale_out[0] = s;
+        if (zero_slot) zero_slot[0] = 0.0f;
+    }
+#pragma unroll
+    for (int i = 0; i < kOnePassPerThread; ++i) {
+        const int idx = i * kEwThreads + threadIdx.x;
+        if (idx < n) q[idx] = (int8_t)quantize_code(v[i], s);
+    }
+}
+
+int quantize_onepass_max() { return kOnePassMax; }
+
+int launch_quantize_onepass(const float* x, int64_t n, float* amax_out, float* scale_out, int8_t* q, float* zero_slot,
+                            hipStream_t st)
+{
+    hipLaunchKernelGGL(quantize_onepass_kernel, dim3(1), dim3(kEwThreads), 0, st, x, (int)n, amax_out, scale_out, q, zero_slot);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
 int launch_quantize_amax(const float* x, int64_t n, const float* amax, int n_amax, float* amax_out, float* scale_out,
                          int8_t* q, float* zero_slot, hipStream_t st)
 {

@@ -28,6 +28,10 @@ int launch_absmax_partial(const float* x, int64_t n, float* partials, int* n_par
 // zero_slot (or null): a float the kernel sets to 0, for the abs-max epilogue of the GEMM that follows.
 int launch_quantize_amax(const float* x, int64_t n, const float* amax, int n_amax, float* amax_out, float* scale_out,
                          int8_t* q, float* zero_slot, hipStream_t st);
+// Tensors of at most quantize_onepass_max() elements: abs-max, scale and quantize in one single-workgroup launch.
+int quantize_onepass_max();
+int launch_quantize_onepass(const float* x, int64_t n, float* amax_out, float* scale_out, int8_t* q, float* zero_slot,
+                            hipStream_t st);
 int launch_scale_from_amax(const float* amax, float* scale_out, hipStream_t st);
 int launch_quantize(const float* x, int64_t n, const float* scale, int8_t* q, hipStream_t st);
 
