@@ -582,6 +582,28 @@ def test_linear_f32_slots_equals_chain(q8):
     assert raw.q8_linear_f32_slots(p, p, 0, p, None, p, 1, 4, 4, 128, p, p, p, None, None, None, 0, None) == 2      # n_slots < 1
 
 
+@pytest.mark.parametrize("n", [4096, 16383, 16384, 16385])
+def test_linear_f32_small_tensor_single_launch_boundary(q8, n):
+    """Around the size up to which one workgroup does abs-max, scale and quantize in one launch: same bytes on
+    both sides of it, also from a 4-byte aligned view."""
+    g = synth.rng(600 + n)
+    x = synth.activations(g, 1, n)
+    x[0, int(g.integers(0, n))] = np.float32(-7.5)                  # the maximum somewhere inside
+    W = synth.weights(g, 3, n)
+    wq, sw = O.quantize_tensor(W)
+    ref = O.linear(x, wq, sw, None)
+    buf = torch.empty(n + 1, device="cuda")
+    buf[1:] = dev(x).reshape(-1)
+    for xd in (dev(x), buf[1:].view(1, n)):
+        xq_work = torch.full((n,), 99, dtype=torch.int8, device="cuda")
+        scal = torch.zeros(q8.SCAL_WORK, device="cuda")
+        y = torch.empty((1, 3), device="cuda")
+        q8.q8_linear_f32(xd, dev(wq), None, dev(np.array([sw], np.float32)), xq_work, scal, y)
+        np.testing.assert_array_equal(host(xq_work).reshape(1, n), ref["xq"])
+        assert host(scal)[0] == np.float32(7.5) and host(scal)[1] == ref["sx"]
+        np.testing.assert_allclose(host(y), ref["y"], rtol=1e-6)
+
+
 @pytest.mark.parametrize("n", [1, 7, 1000, 4_194_304, 12_582_912 + 3])
 def test_linear_f32_scales_and_codes_at_size(q8, n):
     """The fused path's slot-based abs-max: scale and codes bit-exact for sizes from one
