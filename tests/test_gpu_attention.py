@@ -93,6 +93,31 @@ def test_attention(q8, B, S, heads, d, with_mask):
     np.testing.assert_array_equal(host(q3), host(q2))
 
 
+def test_attention_golden_cases(q8, golden_dir):
+    """The hand-worked cases, as given (generic kernel: head widths 1 and 4) and with every head padded with zeros
+    to width 64 (MFMA kernel: zero columns change neither the scores nor the leading columns of the output)."""
+    import json
+    import os
+    with open(os.path.join(golden_dir, "attention_cases.json")) as f:
+        d = json.load(f)
+    for c in d["cases"]:
+        B, S, heads, dh = c["B"], c["S"], c["heads"], c["d"]
+        qkv = np.array(c["qkv"], dtype=np.float32)
+        mask = None if c["mask"] is None else dev(np.array(c["mask"], dtype=np.float32))
+        scale = c["scale"] if c["scale"] is not None else 1.0 / np.sqrt(dh)
+        exp = np.array(c["ctx"])
+        ctx = torch.empty((B * S, heads * dh), device="cuda")
+        q8.q8_attention(dev(qkv), B, S, heads, dh, ctx=ctx, mask=mask, scale=scale)
+        np.testing.assert_allclose(host(ctx), exp, rtol=2e-6, atol=1e-30, err_msg=c["name"])
+        wide = np.zeros((B * S, 3, heads, 64), np.float32)
+        wide[:, :, :, :dh] = qkv.reshape(B * S, 3, heads, dh)
+        ctx = torch.empty((B * S, heads * 64), device="cuda")
+        q8.q8_attention(dev(wide.reshape(B * S, -1)), B, S, heads, 64, ctx=ctx, mask=mask, scale=scale)
+        got = host(ctx).reshape(B * S, heads, 64)
+        np.testing.assert_allclose(got[:, :, :dh].reshape(B * S, -1), exp, rtol=2e-6, atol=1e-30, err_msg=c["name"] + " (width 64)")
+        assert (got[:, :, dh:] == 0).all()
+
+
 def test_attention_random_shapes(q8):
     """Twenty random small problems: sequence lengths around the stage (64) and workgroup (128) sizes, with masks."""
     g = synth.rng(555)

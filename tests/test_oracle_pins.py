@@ -413,6 +413,15 @@ def _attention_library(qkv, B, S, heads, d, mask, scale):
     return (softmax(s, axis=-1) @ v).transpose(0, 2, 1, 3).reshape(B * S, heads * d)
 
 
+def test_attention_golden_cases(golden_dir):
+    d = _load(golden_dir, "attention_cases.json")
+    for c in d["cases"]:
+        qkv = np.array(c["qkv"], dtype=np.float32)
+        mask = None if c["mask"] is None else np.array(c["mask"], dtype=np.float32)
+        got = O.attention(qkv, c["B"], c["S"], c["heads"], c["d"], mask=mask, scale=c["scale"])
+        np.testing.assert_allclose(got, np.array(c["ctx"]), rtol=d["rtol"], atol=1e-30, err_msg=c["name"])
+
+
 def test_attention_hand_cases():
     # one head of width 1, two tokens, scale 1: q = [1, 0], k = [0, ln 3], v = [4, 8]
     #   token 0: scores [0, ln 3] -> weights [1/4, 3/4] -> 1 + 6 = 7;  token 1: scores [0, 0] -> mean(v) = 6
