@@ -152,6 +152,22 @@ def test_attention_sharp_and_flat_softmax(q8):
         close(host(ctx), ref, float(np.abs(qkv[:, 2 * HD:]).max()))
 
 
+def test_attention_masked_leading_keys(q8):
+    """The first 70 keys (more than a stage) carry -10000: the running reference starts 14427 (log2 units) too low and
+    has to jump when the first unmasked key arrives; what was accumulated before must vanish."""
+    g = synth.rng(81)
+    B, S, heads, d = 2, 200, 2, 64
+    HD = heads * d
+    qkv = synth.activations(g, B * S, 3 * HD)
+    mask = np.zeros((B, S), np.float32)
+    mask[:, :70] = -10000.0
+    mask[1, 150:] = -10000.0
+    ref = O.attention(qkv, B, S, heads, d, mask=mask, threads=8)
+    ctx = torch.empty((B * S, HD), device="cuda")
+    q8.q8_attention(dev(qkv), B, S, heads, d, ctx=ctx, mask=dev(mask))
+    close(host(ctx), ref, float(np.abs(qkv[:, 2 * HD:]).max()))
+
+
 def test_attention_closed_forms(q8):
     g = synth.rng(78)
     B, S, heads, d = 2, 150, 3, 64
