@@ -285,8 +285,9 @@ q8_status q8_embedding_sum3_layernorm(const int8_t* word, int64_t Vw, const int8
  * within a few tens; a sequence whose every key carries a large negative mask loses the low bits of
  * its scores to that offset.  Inputs must be finite.
  * B >= 0 (B = 0: nothing written, slots cleared); S >= 1; heads, d >= 1.  d = 64 with 16-byte
- * aligned qkv and ctx (4-byte q_out) takes the MFMA kernel; other widths or alignments take a
- * slower kernel that needs S <= 16384 (Q8_ERR_SHAPE beyond).
+ * aligned qkv and ctx (4-byte q_out) and one sequence of qkv below 2^31 floats takes the MFMA
+ * kernel; other widths or alignments take a slower kernel that needs S <= 16384 (Q8_ERR_SHAPE
+ * beyond).  The softmax runs on a running reference maximum (any S; scores never stored).
  */
 q8_status q8_attention(const float* qkv, int64_t B, int64_t S, int heads, int d,
                        const float* mask, float scale, float* ctx, float* amax_slots,
