@@ -51,7 +51,11 @@ typedef enum {
 #define Q8_AMAX_SLOTS 2048
 
 /* q8_linear epilogue bits. */
-#define Q8_EPI_GELU 1u     /* y <- gelu(y), exact-erf form, in fp32 (GELU stays FP32: Section 3) */
+#define Q8_EPI_GELU 1u     /* y <- gelu(y) = y Phi(y), the erf form (not the tanh form), in fp32 (GELU stays
+                              FP32: Section 3).  Evaluated as max(y,0) - |y| Q(|y|) with log2 of the normal upper
+                              tail Q fitted on [0, 6] by a degree-7 polynomial: absolute error <= 5.3e-7, i.e. the
+                              result agrees with the exact function within 1e-6 absolute + 1e-5 relative, not
+                              within the 1e-6 relative of the FC output itself. */
 #define Q8_EPI_ABSMAX 2u   /* out_amax[0] <- max(out_amax[0], max|y|) over the fp32 outputs of this call */
 #define Q8_EPI_REQUANT 4u  /* y is written as int8 codes Quantize(y | next_scale[0], 127) instead of fp32 */
 
@@ -292,6 +296,16 @@ q8_status q8_embedding_sum3_layernorm(const int8_t* word, int64_t Vw, const int8
 q8_status q8_attention(const float* qkv, int64_t B, int64_t S, int heads, int d,
                        const float* mask, float scale, float* ctx, float* amax_slots,
                        const float* q_scale, int8_t* q_out, void* stream);
+
+/*
+ * ---- tuning / debugging (not part of the method) ----
+ *
+ * Forces the tile shape of the MFMA GEMM behind q8_linear for every later call of this process:
+ * 0 = automatic choice from the shape (the default), 1..6 = one fixed tile variant (tests and
+ * tile sweeps use it to run every variant on every shape).  Process-global and unsynchronised: set it
+ * while no other thread is inside q8_linear.  An unknown variant makes q8_linear return Q8_ERR_LAUNCH.
+ */
+void q8_debug_set_gemm_variant(int variant);
 
 /* Library version string and a short text for a status code (host pointers, static storage). */
 const char* q8_version(void);

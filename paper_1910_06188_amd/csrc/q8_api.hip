@@ -66,7 +66,7 @@ q8_status q8_quantize_amax(const float* x, int64_t n, const float* amax, int n_a
     if (n > 0 && (!x || !q)) return Q8_ERR_NULL;
     if (misaligned(x, 4) || misaligned(amax, 4) || misaligned(amax_out, 4) || misaligned(scale_out, 4))
         return Q8_ERR_ALIGN;
-    if (n == 0) return q8::launch_scale_from_amax(amax, scale_out, as_stream(stream)) ? Q8_ERR_LAUNCH : Q8_OK;
+    // n = 0 still folds the n_amax values and publishes their maximum and the scale (one workgroup, no element read)
     return q8::launch_quantize_amax(x, n, amax, n_amax, amax_out, scale_out, q, nullptr, as_stream(stream)) ? Q8_ERR_LAUNCH
                                                                                                     : Q8_OK;
 }
@@ -139,13 +139,9 @@ q8_status q8_linear_f32_slots(const float* x, const float* amax_slots, int n_slo
     if (s != Q8_OK) return s;
     if (M > 0 && K > 0 && (!x || !xq_work)) return Q8_ERR_NULL;
     if (misaligned(x, 4)) return Q8_ERR_ALIGN;
-    if (M * K == 0) {
-        if (q8::launch_absmax(x, 0, scal_work, scal_work + 1, as_stream(stream))) return Q8_ERR_LAUNCH;
-        if ((flags & Q8_EPI_ABSMAX) && q8::launch_absmax(x, 0, out_amax, nullptr, as_stream(stream))) return Q8_ERR_LAUNCH;
-    } else if (q8::launch_quantize_amax(x, M * K, amax_slots, n_slots, scal_work, scal_work + 1, xq_work,
-                                        (flags & Q8_EPI_ABSMAX) ? out_amax : nullptr, as_stream(stream))) {
-        return Q8_ERR_LAUNCH;
-    }
+    if (q8::launch_quantize_amax(x, M * K, amax_slots, n_slots, scal_work, scal_work + 1, xq_work,
+                                 (flags & Q8_EPI_ABSMAX) ? out_amax : nullptr, as_stream(stream)))
+        return Q8_ERR_LAUNCH;  // M * K = 0: the slots are still folded into scal_work, nothing is quantized
     return q8_linear(xq_work, wq, bias, scal_work + 1, sw, n_groups, M, N, K, y, acc_out, out_amax, next_scale, flags,
                      stream);
 }

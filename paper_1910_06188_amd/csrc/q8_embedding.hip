@@ -108,10 +108,10 @@ __global__ __launch_bounds__(256) void embedding_sum3_kernel(const unsigned* __r
         for (int j = threadIdx.x; j < H4; j += 256) {
             unsigned cw[kEmbRows], cp[kEmbRows], ct[kEmbRows];
 #pragma unroll
-            for (int r = 0; r < kEmbRows; ++r) {
-                cw[r] = wr[r][j];
-                cp[r] = pr[r][j];
-                ct[r] = tr[r][j];
+            for (int r = 0; r < kEmbRows; ++r) {  // a token with a bad id reads nothing (a table may be empty or null)
+                cw[r] = ok[r] ? wr[r][j] : 0u;
+                cp[r] = ok[r] ? pr[r][j] : 0u;
+                ct[r] = ok[r] ? tr[r][j] : 0u;
             }
 #pragma unroll
             for (int r = 0; r < kEmbRows; ++r) {

@@ -345,6 +345,12 @@ __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM*
         b_slot = b_next;
     }
 
+    // The last trips issued the (empty-descriptor) loads of stages KT and KT+1 into the rings; the abs-max
+    // reduction below reuses the first bytes of the rings, so those loads must have landed (they return at
+    // once: nothing is fetched) before anything else is written there.  Asm-issued loads are invisible to the
+    // compiler's own wait insertion.
+    if constexpr (kGen || (kEpi & 2) != 0) __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+
     // Epilogue.  Accumulator register e of lane l is row 8*(e/4) + 4*(l/32) + e%4 and
     // column l%32 of its 32x32 block: 32 lanes store 128 contiguous bytes of one row.
     float next_scale = 0.0f;

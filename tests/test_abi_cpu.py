@@ -71,6 +71,11 @@ def test_host_side_argument_checks(lib):
     assert lib.q8_embedding(p, p, 10, 8, None, 4, p, 0, None, None) == NULL
     assert lib.q8_embedding(p, p, 10, 8, p, 0, p, 0, None, None) == OK                       # T = 0
     assert lib.q8_embedding(p, p, -1, 8, p, 4, p, 0, None, None) == SHAPE
+    # three-table lookup: a table with rows needs its pointer; an empty one may be null (its ids are all bad)
+    lib.q8_embedding_sum3.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, vp, vp, vp, i64, vp, vp, vp]
+    assert lib.q8_embedding_sum3(p, 4, p, 4, None, 2, p, 8, p, p, p, 3, p, None, None) == NULL
+    assert lib.q8_embedding_sum3(p, 4, p, 4, None, 0, p, 8, p, p, p, 0, p, None, None) == OK          # T = 0
+    assert lib.q8_embedding_sum3(p, 4, p, 4, p, -1, p, 8, p, p, p, 3, p, None, None) == SHAPE
     # training side: every check below returns before anything would be launched
     lib.q8_fake_quantize.argtypes = [vp, i64, vp, vp, vp]
     lib.q8_ema_update.argtypes = [vp, C.c_int, C.c_float, vp, vp, vp, vp]

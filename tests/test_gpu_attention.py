@@ -2,9 +2,10 @@
 evaluates it in binary32 (fp32 matrix pipes, running-maximum softmax, exp2), the oracle in binary64.  A score
 is a 64-term binary32 dot product, so its error is a few 1e-7 times its size, the weights inherit that as a
 relative error, and every output -- a convex combination of V rows -- moves by at most that fraction of the
-largest |V| of its head: the bar is |ctx - oracle| <= 1e-5 * max|V| (measured: 0.02-0.08 of it on
-unit-variance inputs, 0.4 of it when the scores reach +-100), not the 1e-6 relative of the FC outputs, which
-an fp32 softmax cannot meet near the zero crossings of its outputs.  The abs-max slots are exact with respect
+largest |V| of its head: the bar is |ctx - oracle| <= 2e-6 * max|V| for inputs of standard deviation up to 1.5
+(measured: 2e-7 to 8e-7 of max|V| there, so a single dropped key out of 384 or a rescale off by a few 1e-6
+fails it) and 1e-5 * max|V| only where the test drives the scores to +-100 (measured 4e-6), not the 1e-6
+relative of the FC outputs, which an fp32 softmax cannot meet near the zero crossings of its outputs.  The abs-max slots are exact with respect
 to the ctx the GPU itself wrote, and int8 codes follow the stage-wise rule: bit-exact with the oracle's
 quantization of that ctx."""
 import numpy as np
@@ -16,7 +17,8 @@ pytestmark = pytest.mark.gpu
 from oracle import q8_oracle as O  # noqa: E402
 from paper_1910_06188_amd import synth  # noqa: E402
 
-TOL = 1e-5
+TOL = 2e-6        # inputs of standard deviation <= 1.5
+TOL_SHARP = 1e-5  # scores of +-100: the binary32 score error grows with the score
 
 
 @pytest.fixture(scope="module")
@@ -35,10 +37,10 @@ def host(t):
     return t.detach().cpu().numpy()
 
 
-def close(got, ref, vmax):
+def close(got, ref, vmax, tol=TOL):
     err = np.abs(got.astype(np.float64) - ref.astype(np.float64)).max()
-    assert err <= TOL * vmax, f"worst error {err:.3e} = {err / (TOL * vmax):.2f} of the tolerance"
-    return err / (TOL * vmax)
+    assert err <= tol * vmax, f"worst error {err:.3e} = {err / (tol * vmax):.2f} of the tolerance"
+    return err / (tol * vmax)
 
 
 def make_mask(g, B, S):
@@ -125,7 +127,7 @@ def test_attention_random_shapes(q8):
         B, heads = int(g.integers(1, 4)), int(g.integers(1, 4))
         S = int(g.choice([1, 2, 31, 63, 64, 65, 100, 127, 128, 129, 191, 192, 193, 255, 257, 300]))
         HD = heads * 64
-        qkv = synth.activations(g, B * S, 3 * HD) * np.float32(g.uniform(0.3, 2.0))
+        qkv = synth.activations(g, B * S, 3 * HD) * np.float32(g.uniform(0.3, 1.5))
         mask = make_mask(g, B, S) if case % 2 else None
         ref = O.attention(qkv, B, S, heads, 64, mask=mask, threads=8)
         ctx = torch.full((B * S, HD), 7.0, device="cuda")
@@ -149,7 +151,7 @@ def test_attention_sharp_and_flat_softmax(q8):
         ref = O.attention(qkv, B, S, heads, d, threads=8)
         ctx = torch.empty((B * S, HD), device="cuda")
         q8.q8_attention(dev(qkv), B, S, heads, d, ctx=ctx)
-        close(host(ctx), ref, float(np.abs(qkv[:, 2 * HD:]).max()))
+        close(host(ctx), ref, float(np.abs(qkv[:, 2 * HD:]).max()), tol=TOL_SHARP if gain > 1.5 else TOL)
 
 
 def test_attention_masked_leading_keys(q8):

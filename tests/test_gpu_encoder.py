@@ -5,7 +5,7 @@ quantize -> attention-output FC -> residual + LayerNorm -> quantize -> FFN1 FC +
 residual + LayerNorm, each quantize + FC pair being one q8_linear_f32_slots call (Section 3: FC layers quantized,
 Softmax / LayerNorm / GELU in FP32; Section 4.1: dynamic scales).
 Each stage is compared with the oracle applied to the input the GPU itself gave that stage, at that stage's own
-bar (int8 codes and scales bit-exact, FC outputs 1e-6 relative, LayerNorm 1e-6 relative, attention 1e-5 of
+bar (int8 codes and scales bit-exact, FC outputs 1e-6 relative, LayerNorm 1e-6 relative, attention 2e-6 of
 max|V|, GELU outputs abs 1e-6 + rel 1e-5): an end-to-end comparison would measure how rounding-boundary flips of
 single codes propagate, not whether any kernel is right.  Shapes: the BERT-Base encoder layer at batch 32 x seq 128,
 and the 12-layer BERT-Base forward at batch 64 x seq 128 with its int8 embedding tables.
@@ -115,7 +115,7 @@ def check_layer(L, w, x_in, x_next, B, S, mask=None):
     r = O.linear(x, L.w_qkv_h, L.s_qkv_h, L.b_qkv_h, threads=THREADS)
     rel_close(qkv, r["y"], 1e-6, what="fused QKV")
     a = O.attention(qkv, B, S, L.heads, H // L.heads, mask=mask, threads=THREADS)
-    assert np.abs(ctx.astype(np.float64) - a).max() <= 1e-5 * np.abs(qkv[:, 2 * H:]).max(), "attention"
+    assert np.abs(ctx.astype(np.float64) - a).max() <= 2e-6 * np.abs(qkv[:, 2 * H:]).max(), "attention"
     r = O.linear(ctx, L.w_o_h, L.s_o_h, L.b_o_h, threads=THREADS)
     rel_close(attn, r["y"], 1e-6, what="attention output")
     rel_close(h1, O.layernorm(x, L.gamma_h[0], L.beta_h[0], residual=attn), 1e-6, 2e-7, what="LayerNorm 1")
@@ -146,6 +146,26 @@ def test_bert_base_encoder_layer_stagewise(q8):
     gpu_layer(q8, L, w, x_in, slots_x, x_next, slots_next, B, S, mask=mask_d)
     torch.cuda.synchronize()
     check_layer(L, w, x_in, x_next, B, S, mask=mask)
+    assert host(slots_next).max() == np.abs(host(x_next)).max()
+
+
+def test_bert_large_encoder_layer_stagewise(q8):
+    """The benchmark's shape: BERT-Large encoder layer, batch 32 x seq 384 = 12288 tokens, hidden 1024, 16 heads,
+    FFN 4096, in the very chain bench.py times as its whole-layer step (each FC one q8_linear_f32_slots call fed by
+    the abs-max slots of the FP32 kernel in front of it).  Every stage in full against the oracle: the four
+    quantizers, the fused QKV, attention-output (12288 x 1024 x 1024), FFN1 + GELU and FFN2 GEMMs, the attention,
+    and both residual + LayerNorm passes at 12288 x 1024."""
+    d = synth.bert_large_layer(seed=3, batch=32, seq=384)
+    B, S, H, F = d["batch"], d["seq"], d["hidden"], d["ffn"]
+    M = B * S
+    L = Layer(q8, d)
+    w = Work(q8, M, H, F)
+    x_in, slots_x = torch.empty((M, H), device="cuda"), torch.zeros(q8.AMAX_SLOTS, device="cuda")
+    q8.q8_layernorm_absmax(dev(d["x"]), L.gamma[1], L.beta[1], x_in, amax_slots=slots_x)
+    x_next, slots_next = torch.empty((M, H), device="cuda"), torch.zeros(q8.AMAX_SLOTS, device="cuda")
+    gpu_layer(q8, L, w, x_in, slots_x, x_next, slots_next, B, S)
+    torch.cuda.synchronize()
+    check_layer(L, w, x_in, x_next, B, S)
     assert host(slots_next).max() == np.abs(host(x_next)).max()
 
 
