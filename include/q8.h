@@ -37,7 +37,8 @@ typedef enum {
     Q8_ERR_SHAPE = 2,  /* negative size, K above Q8_MAX_K, n_groups not dividing N, more than 2^39 output elements */
     Q8_ERR_ALIGN = 3,  /* a pointer breaks the alignment its type needs (4 bytes for float/int32) */
     Q8_ERR_FLAGS = 4,  /* unknown epilogue bit, or a flag without the pointer it needs */
-    Q8_ERR_LAUNCH = 5  /* the HIP runtime refused a launch */
+    Q8_ERR_LAUNCH = 5,    /* the HIP runtime refused a launch */
+    Q8_ERR_TOO_LARGE = 6  /* q8_linear_f32_static: M*K exceeds Q8_STATIC_MAX_CODES */
 } q8_status;
 
 /* Largest reduction length: 128*128*K must stay below 2^31 so that no int8 input,
@@ -46,6 +47,10 @@ typedef enum {
 
 /* Floats of scalar scratch q8_linear_f32 needs: abs-max, scale and up to 2048 partial maxima. */
 #define Q8_SCAL_WORK 2050
+
+/* Largest activation tensor, in elements (M*K), that q8_linear_f32_static takes: its int8 codes live in a
+ * static device array of this many bytes (64 MiB; every FC input of a BERT-Large layer at 12288 tokens fits). */
+#define Q8_STATIC_MAX_CODES (64u << 20)
 
 /* Abs-max slots written by the fused LayerNorm entry points (fp32 each; unused slots are set to 0). */
 #define Q8_AMAX_SLOTS 2048
@@ -139,6 +144,26 @@ q8_status q8_linear_f32(const float* x, const int8_t* wq, const float* bias,
                         int8_t* xq_work, float* scal_work,
                         void* y, int32_t* acc_out, float* out_amax, const float* next_scale,
                         uint32_t epilogue_flags, void* stream);
+
+/*
+ * q8_linear_f32 for callers that cannot allocate and have no workspace to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation and same results as
+ * q8_linear_f32, bit for bit, but the scratch (the partial maxima, max|x|, S_x and the int8 codes of x) lives
+ * in a static device array inside the library, 64 MiB + 16 KiB per GPU, held until the process ends.  The call
+ * allocates and frees nothing (no hipMalloc, no hipFree, no allocating library routine); its first call on a
+ * device looks the array's address up once.
+ *   x, wq, bias, sw, n_groups, M, N, K, y, out_amax, next_scale, epilogue_flags: as q8_linear_f32.
+ *   stats_out fp32[2] or NULL: receives (max|x|, S_x) of this call.
+ *   M*K > Q8_STATIC_MAX_CODES returns Q8_ERR_TOO_LARGE before anything is launched.
+ * Every call on a GPU shares that GPU's array and leaves its contents behind (nothing in it needs clearing
+ * between calls): two calls that overlap in time on one GPU -- different streams, or different host threads --
+ * race on it and must be serialised by the caller.  Calls on one stream are ordered and safe.
+ */
+q8_status q8_linear_f32_static(const float* x, const int8_t* wq, const float* bias,
+                               const float* sw, int n_groups,
+                               int64_t M, int64_t N, int64_t K,
+                               void* y, float* stats_out, float* out_amax, const float* next_scale,
+                               uint32_t epilogue_flags, void* stream);
 
 /*
  * The same layer when the producer of x has already left the abs-max of x behind

@@ -3,7 +3,36 @@
 #include "q8.h"
 #include "q8_launch.h"
 
+#include <mutex>
+
 namespace {
+
+// Scratch of q8_linear_f32_static, the entry point for callers that cannot allocate: Q8_SCAL_WORK floats
+// (abs-max, scale, per-workgroup partial maxima; padded to 16 KiB) followed by the int8 codes of the
+// activation tensor.  Every GPU the library runs on holds its own copy of this array until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress: the device address is looked up
+// once per device (static_scratch below) and everything else -- kernel arguments included -- uses that pointer.
+constexpr size_t kStaticScalBytes = 16384;
+static_assert(kStaticScalBytes >= Q8_SCAL_WORK * sizeof(float), "scalar part of the static scratch");
+static __device__ __align__(256) unsigned char scratch[kStaticScalBytes + Q8_STATIC_MAX_CODES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device, or null if the runtime refuses the lookup.
+unsigned char* static_scratch()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+    }
+    return g_scratch_ptr[dev];
+}
 
 inline bool misaligned(const void* p, unsigned a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
@@ -124,6 +153,28 @@ q8_status q8_linear_f32(const float* x, const int8_t* wq, const float* bias, con
     }
     return q8_linear(xq_work, wq, bias, scal_work + 1, sw, n_groups, M, N, K, y, acc_out, out_amax, next_scale, flags,
                      stream);
+}
+
+q8_status q8_linear_f32_static(const float* x, const int8_t* wq, const float* bias, const float* sw, int n_groups,
+                               int64_t M, int64_t N, int64_t K, void* y, float* stats_out, float* out_amax,
+                               const float* next_scale, uint32_t flags, void* stream)
+{
+    if (M < 0 || K < 0) return Q8_ERR_SHAPE;
+    if (K > 0 && M > (int64_t)Q8_STATIC_MAX_CODES / K) return Q8_ERR_TOO_LARGE;
+    if (misaligned(stats_out, 4)) return Q8_ERR_ALIGN;
+    unsigned char* base = static_scratch();
+    if (!base) return Q8_ERR_LAUNCH;
+    // Nothing in the scratch has to start at zero: the abs-max pass writes every partial-maximum slot the
+    // quantize pass reads, and the codes are written before the GEMM reads them.
+    float* scal = reinterpret_cast<float*>(base);
+    int8_t* codes = reinterpret_cast<int8_t*>(base + kStaticScalBytes);
+    const q8_status s = q8_linear_f32(x, wq, bias, sw, n_groups, M, N, K, codes, scal, y, nullptr, out_amax, next_scale,
+                                      flags, stream);
+    if (s != Q8_OK || !stats_out) return s;
+    // (max|x|, S_x) for the caller: a device-to-device copy of two floats on the same stream
+    return hipMemcpyAsync(stats_out, scal, 2 * sizeof(float), hipMemcpyDeviceToDevice, as_stream(stream)) == hipSuccess
+               ? Q8_OK
+               : Q8_ERR_LAUNCH;
 }
 
 q8_status q8_linear_f32_slots(const float* x, const float* amax_slots, int n_slots, const int8_t* wq, const float* bias,
@@ -289,6 +340,7 @@ const char* q8_status_str(q8_status s)
         case Q8_ERR_ALIGN: return "misaligned pointer";
         case Q8_ERR_FLAGS: return "bad epilogue flags";
         case Q8_ERR_LAUNCH: return "launch failed";
+        case Q8_ERR_TOO_LARGE: return "input exceeds the static scratch of the no-allocation entry point";
     }
     return "unknown status";
 }

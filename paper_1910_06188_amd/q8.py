@@ -25,6 +25,7 @@ _lib = C.CDLL(LIB_PATH)
 OK = 0
 EPI_GELU, EPI_ABSMAX, EPI_REQUANT = 1, 2, 4
 MAX_K = 131071
+STATIC_MAX_CODES = 64 << 20
 SCAL_WORK = 2050
 AMAX_SLOTS = 2048
 
@@ -47,6 +48,8 @@ _lib.q8_layernorm_absmax.argtypes = [_vp, _vp, _vp, _vp, _f32, _i64, _i64, _vp, 
 _lib.q8_embedding_sum3_layernorm.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _f32,
                                              _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.q8_attention.argtypes = [_vp, _i64, _i64, _i32, _i32, _vp, _f32, _vp, _vp, _vp, _vp, _vp]
+_lib.q8_linear_f32_static.argtypes = [_vp, _vp, _vp, _vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _u32, _vp]
+_lib.q8_linear_f32_static.restype = C.c_int
 _lib.q8_linear_f32_slots.argtypes = [_vp, _vp, _i32, _vp, _vp, _vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _u32, _vp]
 for _f in ("q8_linear_f32_slots", "q8_attention", "q8_layernorm_absmax", "q8_embedding_sum3_layernorm", "q8_fake_quantize", "q8_ema_update", "q8_fake_quantize_ema", "q8_ste_backward", "q8_absmax", "q8_scale_from_amax", "q8_quantize", "q8_quantize_amax", "q8_linear", "q8_linear_f32", "q8_embedding",
            "q8_embedding_sum3"):
@@ -145,6 +148,19 @@ def q8_linear_f32(x, wq, bias, sw, xq_work, scal_work, y, n_groups=1, acc_out=No
     _ck(_lib.q8_linear_f32(_ptr(x), _ptr(wq), _ptr(bias), _ptr(sw), n_groups, M, N, K, _ptr(xq_work),
                            _ptr(scal_work), _ptr(y), _ptr(acc_out), _ptr(out_amax), _ptr(next_scale), flags,
                            _stream(stream)), "q8_linear_f32")
+
+
+def q8_linear_f32_static(x, wq, bias, sw, y, n_groups=1, stats_out=None, out_amax=None, next_scale=None, flags=0,
+                         stream=None) -> None:
+    """q8_linear_f32 on the library's static scratch: no workspace arguments, nothing allocated."""
+    M, K = x.shape
+    N, K2 = wq.shape
+    if K != K2 or y.numel() != M * N or (stats_out is not None and stats_out.numel() < 2):
+        raise ValueError("q8_linear_f32_static: shape mismatch")
+    if sw.numel() != n_groups or (bias is not None and bias.numel() != N):
+        raise ValueError("q8_linear_f32_static: scale/bias size mismatch")
+    _ck(_lib.q8_linear_f32_static(_ptr(x), _ptr(wq), _ptr(bias), _ptr(sw), n_groups, M, N, K, _ptr(y), _ptr(stats_out),
+                                  _ptr(out_amax), _ptr(next_scale), flags, _stream(stream)), "q8_linear_f32_static")
 
 
 def q8_linear_f32_slots(x, amax_slots, wq, bias, sw, xq_work, scal_work, y, n_groups=1, acc_out=None, out_amax=None,

@@ -40,8 +40,8 @@ def test_version_and_status_strings(lib):
     lib.q8_version.restype = C.c_char_p
     lib.q8_status_str.restype = C.c_char_p
     assert b"gfx950" in lib.q8_version()
-    texts = {lib.q8_status_str(i) for i in range(6)}
-    assert len(texts) == 6
+    texts = {lib.q8_status_str(i) for i in range(7)}
+    assert len(texts) == 7
 
 
 def test_host_side_argument_checks(lib):
@@ -113,6 +113,12 @@ def test_host_side_argument_checks(lib):
     assert lib.q8_linear_f32_slots(p, p, 1, p, None, p, 1, 4, 4, 128, p, None, p, None, None, None, 0, None) == NULL
     assert lib.q8_linear_f32_slots(p, p + 2, 1, p, None, p, 1, 4, 4, 128, p, p, p, None, None, None, 0, None) == ALIGN
     assert lib.q8_linear_f32_slots(None, p, 1, p, None, p, 1, 4, 4, 128, p, p, p, None, None, None, 0, None) == NULL
+    # the no-allocation variant refuses what its static scratch cannot hold before it touches the device
+    lib.q8_linear_f32_static.argtypes = [vp, vp, vp, vp, C.c_int, i64, i64, i64, vp, vp, vp, vp, C.c_uint32, vp]
+    TOO_LARGE = 6
+    assert lib.q8_linear_f32_static(p, p, None, p, 1, (64 << 20) // 1024 + 1, 8, 1024, p, None, None, None, 0, None) == TOO_LARGE
+    assert lib.q8_linear_f32_static(p, p, None, p, 1, -1, 8, 1024, p, None, None, None, 0, None) == SHAPE
+    assert lib.q8_linear_f32_static(p, p, None, p, 1, 4, 8, 128, p, p + 2, None, None, 0, None) == ALIGN
     # FP32 attention between the QKV and attention-output FC layers
     lib.q8_attention.argtypes = [vp, i64, i64, C.c_int, C.c_int, vp, C.c_float, vp, vp, vp, vp, vp]
     assert lib.q8_attention(p, -1, 8, 2, 64, None, 0.125, p, None, None, None, None) == SHAPE
