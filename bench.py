@@ -34,9 +34,21 @@ METRIC = "int8 TOPS + % MFMA peak on BERT FC GEMMs; tokens/s per quantized BERT 
 INT8_PEAK_TOPS = 5033.0      # MI355X published dense int8 matrix peak
 FP32_PEAK_TFLOPS = 157.3    # MI355X published fp32 matrix peak
 HBM_PEAK_GBS = 8000.0
-# HBM-side bytes per launch of the FFN2 GEMM at the default workload, from the two rocprofv3 --pmc runs summarised in
-# profiles/bench_bert_large_layer_pmc_traffic.txt (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, calibrated on a 256 MiB copy)
-FFN2_TRAFFIC_BYTES = 134.5e6
+PREWARM_STEPS = 200         # untimed steps in front of --warmup: the clock takes a few dozen launches to settle after idle
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "bench_bert_large_layer_pmc_traffic.txt")
+
+
+def profiled_traffic(key):
+    """HBM-side bytes per launch of a kernel as the committed rocprofv3 --pmc summary recorded them (FETCH_SIZE and
+    WRITE_SIZE runs, scaled on a copy of known size).  Counters cannot be read from inside this process, so the figure
+    is the profile's, named as such in the JSON; None if the summary is missing or has no such line."""
+    try:
+        for line in open(TRAFFIC_PROFILE):
+            if line.startswith("traffic_bytes_per_launch " + key + " "):
+                return float(line.split("=")[1].split()[0])
+    except OSError:
+        pass
+    return None
 
 
 def parse():
@@ -115,25 +127,33 @@ class Layer:
                               flags=flags)
 
     def step(self, ev=None):
-        """The timed hot path.  ev: optional (start, end) event pair recorded around FFN2's GEMM."""
+        """The timed hot path.  ev: optional dict of (start, end) event pairs keyed "qkv", "attn_out", "ffn1", "ffn2",
+        recorded around that FC's GEMM launch alone (each dynamic FC is the quantizer of Section 4.1 -- two launches --
+        followed by the GEMM: the same three launches q8_linear_f32 makes)."""
         q8 = self.q8
         M, H, F = self.M, self.H, self.F
+
+        def gemm(name, *a, **kw):
+            if ev is not None and name in ev:
+                ev[name][0].record()
+            q8.q8_linear(*a, **kw)
+            if ev is not None and name in ev:
+                ev[name][1].record()
         q8.q8_embedding_sum3(self.tables[0], self.tables[1], self.tables[2], self.table_scales, self.ids[0],
                              self.ids[1], self.ids[2], self.emb, err_flag=self.err)
-        self._fc_dyn(self.x, H, self.w_qkv, self.s_qkv, self.b_qkv, self.qkv, n_groups=3)
-        self._fc_dyn(self.ctx, H, self.w_o, self.s_o, self.b_o, self.attn_out)
-        # FFN1: GELU and the abs-max of the GELU output come out of the GEMM epilogue
-        g_amax, g_scale = self.gscal[0:1], self.gscal[1:2]          # the one-call FC resets the abs-max slot itself
-        self._fc_dyn(self.h1, H, self.w_1, self.s_1, self.b_1, self.g, flags=q8.EPI_GELU | q8.EPI_ABSMAX,
-                     out_amax=g_amax)
+        xq, sx = self.xq[: M * H].view(M, H), self.scal[1:2]
+        q8.q8_quantize_dynamic(self.x, xq, self.scal)
+        gemm("qkv", xq, self.w_qkv, self.b_qkv, sx, self.s_qkv, self.qkv, n_groups=3)
+        q8.q8_quantize_dynamic(self.ctx, xq, self.scal)
+        gemm("attn_out", xq, self.w_o, self.b_o, sx, self.s_o, self.attn_out)
+        # FFN1: GELU and the abs-max of the GELU output come out of the GEMM epilogue (the quantizer clears the slot)
+        g_amax, g_scale = self.gscal[0:1], self.gscal[1:2]
+        q8.q8_quantize_dynamic(self.h1, xq, self.scal, zero_slot=g_amax)
+        gemm("ffn1", xq, self.w_1, self.b_1, sx, self.s_1, self.g, out_amax=g_amax, flags=q8.EPI_GELU | q8.EPI_ABSMAX)
         # FFN2: S_x from the fused abs-max inside the quantize pass, then the GEMM
         xq = self.xq[: M * F].view(M, F)
         q8.q8_quantize_amax(self.g, g_amax, g_scale, xq)
-        if ev is not None:
-            ev[0].record()
-        q8.q8_linear(xq, self.w_2, self.b_2, g_scale, self.s_2, self.out)
-        if ev is not None:
-            ev[1].record()
+        gemm("ffn2", xq, self.w_2, self.b_2, g_scale, self.s_2, self.out)
 
     def calibrate_static(self):
         """Stored activation scales for the static mode (Eq. 4 keeps such a scale from training; here the scale a
@@ -310,6 +330,41 @@ def cpu_baseline(d, sample_tokens):
                 tokens_per_s=M / dt)
 
 
+def gemm_bound(M, N, K, out_bytes):
+    """Roofline of one FC GEMM from its algorithmic work: int8 ops 2 M N K against the published matrix peak, bytes
+    M K + N K + out_bytes M N + 4 N (codes, weights, output, bias) against the published HBM rate."""
+    ops = 2.0 * M * N * K
+    nbytes = float(M * K + N * K + out_bytes * M * N + 4 * N)
+    t_mfma, t_hbm = ops / (INT8_PEAK_TOPS * 1e12), nbytes / (HBM_PEAK_GBS * 1e9)
+    return dict(ops=ops, bytes=nbytes, bound="mfma" if t_mfma >= t_hbm else "hbm", bound_us=max(t_mfma, t_hbm) * 1e6)
+
+
+def timed(torch, fn, n, warm):
+    """Mean wall time of fn() in seconds over n calls after warm untimed ones, bracketed by synchronisations."""
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / n
+
+
+def event_us(torch, fn, reps, warm=3):
+    """Mean duration of fn(i) in microseconds between two events on the launch stream."""
+    for i in range(warm):
+        fn(i)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for i in range(reps):
+        fn(i)
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) * 1e3 / reps
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -326,11 +381,13 @@ def main():
     ids = synth.token_ids(seed=6, batch=args.batch, seq=args.seq)
     layer = Layer(q8, torch, d, tables, ids)
     layer.glue_once()
+    M, H, F = layer.M, layer.H, layer.F
 
-    for _ in range(args.warmup):
+    # ---- the timed region: K steps of the dynamic-quantization hot path -------------------------------------------------
+    for _ in range(PREWARM_STEPS + args.warmup):
         layer.step()
     torch.cuda.synchronize()
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    evs = [{"ffn1": (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))} for _ in range(args.steps)]
     t0 = time.perf_counter()
     for i in range(args.steps):
         layer.step(evs[i])
@@ -346,11 +403,15 @@ def main():
 
     ms_per_step = dt / args.steps * 1e3
     tops = layer.gemm_ops / (dt / args.steps) / 1e12
-    tokens_per_s = layer.M / (dt / args.steps)
-    # dominant kernel: the FFN2 GEMM (12288 x 1024 x 4096), timed with events on the launch stream
-    ffn2_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
-    ffn2_ops = 2.0 * layer.M * layer.H * layer.F
-    ffn2_tops = ffn2_ops / (ffn2_ms * 1e-3) / 1e12
+    tokens_per_s = M / (dt / args.steps)
+    # the step's longest kernel: the FFN1 GEMM with GELU + abs-max epilogue (12288 x 4096 x 1024, 201 MB of fp32 out),
+    # bound by its HBM write; timed with events on the launch stream around that launch in every timed step
+    shapes = {"qkv": ("fused QKV", 3 * H, H, 4), "attn_out": ("attention-output", H, H, 4),
+              "ffn1": ("FFN1 + GELU + abs-max", F, H, 4), "ffn2": ("FFN2", H, F, 4)}
+    ffn1_us = float(np.mean([e["ffn1"][0].elapsed_time(e["ffn1"][1]) for e in evs])) * 1e3
+    rb = gemm_bound(M, F, H, 4)
+    ffn1_gbs = rb["bytes"] / (ffn1_us * 1e-6) / 1e9
+    default_shape = (args.batch, args.seq) == (32, 384)
     out = {
         "metric": METRIC, "value": round(tops, 2), "unit": "int8 TOPS", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
@@ -358,75 +419,81 @@ def main():
         "config": {"workload": "BERT-Large encoder layer, batch %d x seq %d (BASELINE configs[3]): six quantized FC "
                                "layers (fused QKV, attn-out, FFN1+GELU, FFN2) with dynamic per-tensor scales, plus "
                                "the int8 3-table embedding gather" % (args.batch, args.seq),
-                   "tokens": layer.M, "hidden": layer.H, "ffn": layer.F, "fp32_glue_timed": False},
+                   "tokens": M, "hidden": H, "ffn": F, "fp32_glue_timed": False, "prewarm_steps": PREWARM_STEPS},
         "tokens_per_s": round(tokens_per_s, 1),
         "pct_int8_mfma_peak_whole_step": round(100.0 * tops / INT8_PEAK_TOPS, 2),
-        "roofline": {"bound": "mfma", "kernel": "gemm_mfma_kernel (FFN2 12288x1024x4096, fp32 out)",
-                     "achieved": round(ffn2_tops, 1), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": round(ffn2_tops / INT8_PEAK_TOPS, 4), "avg_launch_us": round(ffn2_ms * 1e3, 2),
-                     "traffic": FFN2_TRAFFIC_BYTES if (args.batch, args.seq) == (32, 384) else None,
-                     "traffic_unit": "bytes per launch (algorithmic: 104.9e6)",
-                     "measured_mfma_ceiling_real_operands_tops": 3400.0},
+        "roofline": {"bound": "hbm", "kernel": "gemm_mfma_kernel, FFN1 %dx%dx%d + GELU + abs-max, fp32 out (the step's longest kernel)" % (M, F, H),
+                     "achieved": round(ffn1_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(ffn1_gbs / HBM_PEAK_GBS, 4), "avg_launch_us": round(ffn1_us, 2),
+                     "algorithmic_bytes": rb["bytes"], "int8_tops": round(rb["ops"] / ffn1_us / 1e6, 1),
+                     "pct_int8_mfma_peak": round(100.0 * rb["ops"] / ffn1_us / 1e6 / INT8_PEAK_TOPS, 2),
+                     "traffic": profiled_traffic("FFN1_GELU_ABSMAX") if default_shape else None,
+                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary under profiles/ (not measured in this run)"},
     }
-    # The same FFN2 launch on constant operands (every code 1): identical instruction stream and
-    # traffic, far fewer bits toggling in the multipliers.  The gap to the figure above is the
-    # chip's power management, not the kernel's structure.
-    xq1 = torch.ones((layer.M, layer.F), dtype=torch.int8, device="cuda")
-    w1c = torch.ones((layer.H, layer.F), dtype=torch.int8, device="cuda")
+    # ---- every FC GEMM of the step against its own roofline: a second pass of steps with events around all four ---------
+    n_pg = max(10, min(args.steps, 200))
+    pevs = [{k: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for k in shapes} for _ in range(n_pg)]
+    for i in range(n_pg):
+        layer.step(pevs[i])
+    torch.cuda.synchronize()
+    per_gemm = {}
+    for k, (label, N_, K_, ob) in shapes.items():
+        us = float(np.mean([e[k][0].elapsed_time(e[k][1]) for e in pevs])) * 1e3
+        b = gemm_bound(M, N_, K_, ob)
+        per_gemm[label + " %dx%dx%d" % (M, N_, K_)] = {
+            "us": round(us, 2), "bound": b["bound"], "bound_us": round(b["bound_us"], 2), "frac_of_roofline": round(b["bound_us"] / us, 4),
+            "int8_tops": round(b["ops"] / us / 1e6, 1), "pct_int8_mfma_peak": round(100.0 * b["ops"] / us / 1e6 / INT8_PEAK_TOPS, 2),
+            "algorithmic_GBps": round(b["bytes"] / us / 1e3, 1)}
+    out["per_gemm"] = per_gemm
+    # ---- what the chip itself sustains, measured in this run: the matrix pipes on register-resident operands (no memory
+    # traffic; Gaussian codes as the layer's, and all-zero ones) and the HBM on streaming passes larger than every cache --------
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    gauss = torch.clamp(torch.round(torch.randn(65536, device="cuda") * 25.0), -127, 127).to(torch.int8)
+    zeros = torch.zeros(65536, dtype=torch.int8, device="cuda")
+    ceil = {}
+    for name, ops_t in (("gaussian_codes", gauss), ("zero_codes", zeros)):
+        n_ops = [0.0]
+
+        def run(i, ops_t=ops_t):
+            n_ops[0] = q8.debug_mfma_rate(ops_t, 8000, 256, sink)
+        us = event_us(torch, run, 10)
+        ceil["mfma_i8_register_resident_" + name] = {"int8_tops": round(n_ops[0] / us / 1e6, 1),
+                                                     "frac_of_published_peak": round(n_ops[0] / us / 1e6 / INT8_PEAK_TOPS, 4)}
+    big = [torch.empty(M * F, device="cuda") for _ in range(5)]          # 5 x 201 MB: beyond the 256 MB Infinity Cache
+    for t in big:
+        t.normal_()
+    nb = big[0].numel() * 4
+    us = event_us(torch, lambda i: q8.debug_stream_copy(big[i % 5], big[(i + 1) % 5]), 20)
+    ceil["hbm_stream_copy_201MB"] = {"us": round(us, 1), "GBps_read_plus_write": round(2.0 * nb / us / 1e3, 1), "frac_of_8TBps": round(2.0 * nb / us / 1e3 / HBM_PEAK_GBS, 3)}
+    us = event_us(torch, lambda i: q8.debug_stream_copy(None, big[i % 5]), 20)
+    ceil["hbm_stream_fill_201MB"] = {"us": round(us, 1), "GBps_write": round(nb / us / 1e3, 1), "frac_of_8TBps": round(nb / us / 1e3 / HBM_PEAK_GBS, 3)}
+    out["measured_ceilings"] = ceil
+    # The FFN2 launch on constant operands (every code 1): identical instruction stream and traffic, far fewer bits toggling
+    # in the multipliers.  The gap to its per_gemm figure is the chip's power management, not the kernel's structure.
+    xq1 = torch.ones((M, F), dtype=torch.int8, device="cuda")
+    w1c = torch.ones((H, F), dtype=torch.int8, device="cuda")
     cs = torch.ones(2, device="cuda")
-    for _ in range(10):
-        q8.q8_linear(xq1, w1c, layer.b_2, cs[0:1], cs[1:2], layer.out)
-    torch.cuda.synchronize()
-    ce = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    ce[0].record()
-    for _ in range(50):
-        q8.q8_linear(xq1, w1c, layer.b_2, cs[0:1], cs[1:2], layer.out)
-    ce[1].record()
-    torch.cuda.synchronize()
-    const_ms = ce[0].elapsed_time(ce[1]) / 50
-    out["roofline"]["same_launch_constant_operands"] = {"avg_launch_us": round(const_ms * 1e3, 2),
-                                                        "achieved": round(ffn2_ops / (const_ms * 1e-3) / 1e12, 1),
-                                                        "frac": round(ffn2_ops / (const_ms * 1e-3) / 1e12 / INT8_PEAK_TOPS, 4)}
+    const_us = event_us(torch, lambda i: q8.q8_linear(xq1, w1c, layer.b_2, cs[0:1], cs[1:2], layer.out), 50, warm=10)
+    ffn2_ops = 2.0 * M * H * F
+    out["ffn2_constant_operands"] = {"us": round(const_us, 2), "int8_tops": round(ffn2_ops / const_us / 1e6, 1),
+                                     "pct_int8_mfma_peak": round(100.0 * ffn2_ops / const_us / 1e6 / INT8_PEAK_TOPS, 2)}
     del xq1, w1c
-    # the paper's own inference mode (stored activation scales, Eq. 4), reported beside the headline
+    # ---- the paper's own inference mode (stored activation scales, Eq. 4), reported beside the headline ---------------------
     layer.calibrate_static()
     n_static = max(10, args.steps // 4)
-    n_warm = max(5, args.warmup // 4)          # the clock settles over the first few dozen launches of a new kernel mix
-    for _ in range(n_warm):
-        layer.step_static()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(n_static):
-        layer.step_static()
-    torch.cuda.synchronize()
-    dts = (time.perf_counter() - t0) / n_static
+    n_warm = max(20, args.warmup // 4)
+    dts = timed(torch, layer.step_static, n_static, n_warm)
     out["static_scale_mode"] = {"ms_per_step": round(dts * 1e3, 4), "int8_tops": round(layer.gemm_ops / dts / 1e12, 2),
-                                "tokens_per_s": round(layer.M / dts, 1), "steps": n_static,
+                                "tokens_per_s": round(M / dts, 1), "steps": n_static,
                                 "note": "stored activation scales: no abs-max passes; FFN1 emits int8 (GELU + "
                                         "requantize epilogue) straight into FFN2"}
-    # the same layer with the FP32 glue around the FCs fused into the library (embedding + LayerNorm, residual +
-    # LayerNorm twice; each hands the abs-max of its output to the next quantizer): more work per step, reported beside
-    for _ in range(n_warm):
-        layer.step_fused()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(n_static):
-        layer.step_fused()
-    torch.cuda.synchronize()
-    dtf = (time.perf_counter() - t0) / n_static
-    out["fused_layernorm_mode"] = {"ms_per_step": round(dtf * 1e3, 4), "tokens_per_s": round(layer.M / dtf, 1), "steps": n_static,
+    dtf = timed(torch, layer.step_fused, n_static, n_warm)
+    out["fused_layernorm_mode"] = {"ms_per_step": round(dtf * 1e3, 4), "tokens_per_s": round(M / dtf, 1), "steps": n_static,
                                    "note": "dynamic scales; adds embedding+LayerNorm and the layer's two residual+LayerNorm "
                                            "passes to the step and drops the abs-max passes of QKV and FFN1 (their abs-max "
                                            "comes out of the LayerNorm kernels)"}
-    for _ in range(n_warm):
-        layer.step_fused_static()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(n_static):
-        layer.step_fused_static()
-    torch.cuda.synchronize()
-    dtfs = (time.perf_counter() - t0) / n_static
-    out["fused_layernorm_static_mode"] = {"ms_per_step": round(dtfs * 1e3, 4), "tokens_per_s": round(layer.M / dtfs, 1), "steps": n_static,
+    dtfs = timed(torch, layer.step_fused_static, n_static, n_warm)
+    out["fused_layernorm_static_mode"] = {"ms_per_step": round(dtfs * 1e3, 4), "tokens_per_s": round(M / dtfs, 1), "steps": n_static,
                                           "note": "stored scales; the embedding block and both residual+LayerNorm passes also "
                                                   "write the int8 codes of their output, so QKV and FFN1 have no quantize pass"}
     # the whole encoder layer, FP32 softmax attention included (fp32 matrix pipes: 4 S^2 d flops per head), every
@@ -441,100 +508,106 @@ def main():
     torch.cuda.synchronize()
     dtl = (time.perf_counter() - t0) / n_static
     attn_ms = sum(a.elapsed_time(b) for a, b in aev) / n_static
-    attn_flops = 4.0 * layer.batch * layer.heads * layer.seq * layer.seq * (layer.H // layer.heads)
-    out["encoder_layer_mode"] = {"ms_per_step": round(dtl * 1e3, 4), "tokens_per_s": round(layer.M / dtl, 1), "steps": n_static,
+    attn_flops = 4.0 * layer.batch * layer.heads * layer.seq * layer.seq * (H // layer.heads)
+    out["encoder_layer_mode"] = {"ms_per_step": round(dtl * 1e3, 4), "tokens_per_s": round(M / dtl, 1), "steps": n_static,
                                  "attention": {"avg_launch_us": round(attn_ms * 1e3, 2), "dtype": "f32",
                                                "achieved_tflops": round(attn_flops / (attn_ms * 1e-3) / 1e12, 1),
                                                "frac_of_fp32_mfma_peak": round(attn_flops / (attn_ms * 1e-3) / 1e12 / FP32_PEAK_TFLOPS, 4)},
                                  "note": "dynamic scales; QKV FC, FP32 softmax attention, attention-output FC, residual + "
                                          "LayerNorm, FFN1 + GELU, FFN2, residual + LayerNorm; no embedding block"}
-    for _ in range(n_warm):
-        layer.step_layer_static()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(n_static):
-        layer.step_layer_static()
-    torch.cuda.synchronize()
-    dtls = (time.perf_counter() - t0) / n_static
-    out["encoder_layer_static_mode"] = {"ms_per_step": round(dtls * 1e3, 4), "tokens_per_s": round(layer.M / dtls, 1), "steps": n_static,
+    dtls = timed(torch, layer.step_layer_static, n_static, n_warm)
+    out["encoder_layer_static_mode"] = {"ms_per_step": round(dtls * 1e3, 4), "tokens_per_s": round(M / dtls, 1), "steps": n_static,
                                         "note": "stored scales; seven kernels: the attention kernel and both LayerNorms write the "
                                                 "int8 codes the next FC reads, FFN1 writes int8 through its epilogue"}
-    # the two FFN GEMMs on their own, launched back to back: once on one set of buffers (operands and output stay in
+
+    # ---- the two FFN GEMMs on their own, launched back to back: once on one set of buffers (operands and output stay in
     # the caches) and once rotating through sets that together exceed the 256 MB Infinity Cache
     def gemm_alone(N, K, flags, int8_out):
-        per_set = layer.M * K + N * K + (1 if int8_out else 4) * layer.M * N
+        per_set = M * K + N * K + (1 if int8_out else 4) * M * N
         R = int(1.0e9 // per_set) + 2
-        sets = [(torch.randint(-127, 128, (layer.M, K), dtype=torch.int8, device="cuda"),
+        sets = [(torch.randint(-127, 128, (M, K), dtype=torch.int8, device="cuda"),
                  torch.randint(-127, 128, (N, K), dtype=torch.int8, device="cuda"),
-                 torch.empty((layer.M, N), dtype=torch.int8 if int8_out else torch.float32, device="cuda")) for _ in range(R)]
+                 torch.empty((M, N), dtype=torch.int8 if int8_out else torch.float32, device="cuda")) for _ in range(R)]
         bb = torch.zeros(N, device="cuda")
-        sc = torch.tensor([24.0, 1200.0, 20.0, 0.0], device="cuda")
+        scl = torch.tensor([24.0, 1200.0, 20.0, 0.0], device="cuda")
         res = {}
         for mode in ("cache_warm", "rotating"):
             def launch(i):
                 xq_, wq_, y_ = sets[i % R] if mode == "rotating" else sets[0]
-                q8.q8_linear(xq_, wq_, bb, sc[0:1], sc[1:2], y_, out_amax=sc[3:4] if flags & 2 else None,
-                             next_scale=sc[2:3] if flags & 4 else None, flags=flags)
-            for i in range(R + 2):
-                launch(i)
-            torch.cuda.synchronize()
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            n = 4 * R
-            a.record()
-            for i in range(n):
-                launch(i)
-            b.record()
-            torch.cuda.synchronize()
-            us = a.elapsed_time(b) * 1e3 / n
-            res[mode] = {"us": round(us, 1), "int8_tops": round(2.0 * layer.M * N * K / us / 1e6, 1)}
+                q8.q8_linear(xq_, wq_, bb, scl[0:1], scl[1:2], y_, out_amax=scl[3:4] if flags & 2 else None,
+                             next_scale=scl[2:3] if flags & 4 else None, flags=flags)
+            us = event_us(torch, launch, 4 * R, warm=R + 2)
+            res[mode] = {"us": round(us, 1), "int8_tops": round(2.0 * M * N * K / us / 1e6, 1)}
         return res
     out["gemm_alone"] = {
-        "FFN2 12288x1024x4096 fp32 out": gemm_alone(layer.H, layer.F, 0, False),
-        "FFN1 12288x4096x1024 fp32 out": gemm_alone(layer.F, layer.H, 0, False),
-        "FFN1 12288x4096x1024 GELU + requantize, int8 out": gemm_alone(layer.F, layer.H, 5, True),
+        "FFN2 12288x1024x4096 fp32 out": gemm_alone(H, F, 0, False),
+        "FFN1 12288x4096x1024 fp32 out": gemm_alone(F, H, 0, False),
+        "FFN1 12288x4096x1024 GELU + requantize, int8 out": gemm_alone(F, H, 5, True),
     }
-    # the memory-bound kernels on their own: achieved bytes/s against the 8 TB/s of the HBM (algorithmic bytes)
+    # ---- the memory-bound kernels on their own, each launch on a different 201 MB (or 50 MB) tensor of a set larger than
+    # the 256 MB Infinity Cache, so the rates are the HBM's: achieved algorithmic bytes/s against the published 8 TB/s
     def hbm_rate(fn, nbytes, reps=20):
-        for _ in range(3):
-            fn()
-        torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(reps):
-            fn()
-        b.record()
-        torch.cuda.synchronize()
-        us = a.elapsed_time(b) * 1e3 / reps
-        return {"us_per_call": round(us, 1), "GBps": round(nbytes / us / 1e3, 1), "frac_of_8TBps": round(nbytes / us / 1e3 / 8000.0, 3)}
-    big, nbig = layer.g, layer.g.numel()
+        us = event_us(torch, fn, reps)
+        return {"us_per_call": round(us, 1), "GBps": round(nbytes / us / 1e3, 1), "frac_of_8TBps": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 3)}
+    nbig = M * F
     xq_big = layer.xq[:nbig]
+    mid = [torch.randn((M, H), device="cuda") for _ in range(12)]         # 12 x 50 MB
+    mid_out = [torch.empty((M, H), device="cuda") for _ in range(6)]
     out["hbm_kernels"] = {
-        "q8_absmax fp32[12288,4096] (4 B/elt; 3 launches)": hbm_rate(lambda: q8.q8_absmax(big, layer.gscal[0:1], layer.gscal[1:2]), 4.0 * nbig),
-        "q8_quantize fp32[12288,4096] (5 B/elt)": hbm_rate(lambda: q8.q8_quantize(big, layer.gscal[1:2], xq_big), 5.0 * nbig),
+        "q8_absmax fp32[12288,4096] (4 B/elt; 3 launches)": hbm_rate(lambda i: q8.q8_absmax(big[i % 5], layer.gscal[0:1], layer.gscal[1:2]), 4.0 * nbig),
+        "q8_quantize fp32[12288,4096] (5 B/elt)": hbm_rate(lambda i: q8.q8_quantize(big[i % 5], layer.gscal[1:2], xq_big), 5.0 * nbig),
+        "q8_quantize_dynamic fp32[12288,1024] (9 B/elt; 2 launches)": hbm_rate(lambda i: q8.q8_quantize_dynamic(mid[i % 12], layer.xq[: M * H], layer.scal), 9.0 * M * H),
         "q8_embedding_sum3 12288 tokens x 1024 (3 int8 rows in, fp32 row out)": hbm_rate(
-            lambda: q8.q8_embedding_sum3(layer.tables[0], layer.tables[1], layer.tables[2], layer.table_scales, layer.ids[0],
-                                         layer.ids[1], layer.ids[2], layer.emb, err_flag=layer.err), layer.M * (3.0 * layer.H + 12 + 4.0 * layer.H)),
+            lambda i: q8.q8_embedding_sum3(layer.tables[0], layer.tables[1], layer.tables[2], layer.table_scales, layer.ids[0],
+                                           layer.ids[1], layer.ids[2], mid_out[i % 6], err_flag=layer.err), M * (3.0 * H + 12 + 4.0 * H)),
         "q8_layernorm_absmax fp32[12288,1024] + residual (12 B/elt)": hbm_rate(
-            lambda: q8.q8_layernorm_absmax(layer.x, layer.ln_g, layer.ln_b, layer.h1f, residual=layer.attn_out, amax_slots=layer.slots_h),
-            12.0 * layer.M * layer.H),
+            lambda i: q8.q8_layernorm_absmax(mid[i % 12], layer.ln_g, layer.ln_b, mid_out[i % 6], residual=mid[(i + 5) % 12], amax_slots=layer.slots_h),
+            12.0 * M * H),
+        "note": "every launch reads a tensor no earlier launch of the loop left in the 256 MB Infinity Cache",
     }
+    del mid, mid_out
     # training-side quantizer (Section 2.2 / Eq. 4): abs-max, moving-average step and fake quantization
     # of the FFN2-input-sized activation; bound by HBM (4 B read for the abs-max, 4 B + 4 B for the rest)
-    xs = layer.g
-    fq = torch.empty_like(xs)
     ema_state = torch.zeros(2, device="cuda")
-    n_tr = max(10, args.steps // 4)
-    for _ in range(3):
-        q8.q8_fake_quantize_ema(xs, 0.9, ema_state, layer.scal, fq)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(n_tr):
-        q8.q8_fake_quantize_ema(xs, 0.9, ema_state, layer.scal, fq)
-    torch.cuda.synchronize()
-    dtt = (time.perf_counter() - t0) / n_tr
-    out["training_side"] = {"op": "q8_fake_quantize_ema on fp32[%d, %d]" % tuple(xs.shape), "us_per_call": round(dtt * 1e6, 1),
-                            "algorithmic_GBps": round(12.0 * xs.numel() / dtt / 1e9, 1), "bound": "hbm",
-                            "frac_of_8TBps": round(12.0 * xs.numel() / dtt / 8e12, 3)}
+    us = event_us(torch, lambda i: q8.q8_fake_quantize_ema(big[i % 4], 0.9, ema_state, layer.scal, big[4]), 12)
+    out["training_side"] = {"op": "q8_fake_quantize_ema on fp32[%d, %d]" % (M, F), "us_per_call": round(us, 1),
+                            "algorithmic_GBps": round(12.0 * nbig / us / 1e3, 1), "bound": "hbm",
+                            "frac_of_8TBps": round(12.0 * nbig / us / 1e3 / HBM_PEAK_GBS, 3)}
+    del big
+    # ---- the other BASELINE configurations, driver-visible: C1 one FC at 16 tokens, C3 one BERT-Base encoder layer at
+    # 32 x 128 tokens, C5 the 12-layer BERT-Base forward at 64 x 128 tokens with its int8 embedding block (dynamic scales,
+    # every operation in the library; the 12 layers reuse one set of weights, which does not change the work)
+    c1 = synth.single_fc(0)
+    x1 = torch.from_numpy(c1["x"]).cuda()
+    w1q = torch.empty((768, 768), dtype=torch.int8, device="cuda")
+    s1 = torch.zeros(2, device="cuda")
+    q8.q8_absmax(torch.from_numpy(c1["W"]).cuda(), s1[0:1], s1[1:2])
+    q8.q8_quantize(torch.from_numpy(c1["W"]).cuda(), s1[1:2], w1q)
+    b1 = torch.from_numpy(c1["b"]).cuda()
+    y1, xq1_ = torch.empty((16, 768), device="cuda"), torch.empty(16 * 768, dtype=torch.int8, device="cuda")
+    us = event_us(torch, lambda i: q8.q8_linear_f32(x1, w1q, b1, s1[1:2], xq1_, layer.scal, y1), 200, warm=20)
+    out["c1_single_fc_16x768x768"] = {"us_per_dynamic_fc_call": round(us, 2), "launches": 2}
+    base = {}
+    for key, batch in (("c3_bert_base_encoder_layer_32x128", 32), ("c5_bert_base_12_layer_forward_64x128", 64)):
+        db = synth.bert_base_layer(seed=2, batch=batch, seq=128)
+        lb = Layer(q8, torch, db, synth.embedding_tables(seed=5, hidden=768), synth.token_ids(seed=6, batch=batch, seq=128))
+        lb.glue_once()
+        lb.step_fused()
+        lb.step_layer()
+        torch.cuda.synchronize()
+        if batch == 32:
+            t = timed(torch, lb.step_layer, 100, 30)
+            base[key] = {"us_per_layer": round(t * 1e6, 1), "tokens_per_s": round(lb.M / t, 1)}
+        else:
+            def forward(lb=lb):
+                q8.q8_embedding_sum3_layernorm(lb.tables[0], lb.tables[1], lb.tables[2], lb.table_scales, lb.ids[0], lb.ids[1],
+                                               lb.ids[2], lb.ln_g, lb.ln_b, lb.x_in, amax_slots=lb.slots_x, err_flag=lb.err)
+                for _ in range(12):
+                    lb.step_layer()
+            t = timed(torch, forward, 30, 10)
+            base[key] = {"ms_per_forward": round(t * 1e3, 3), "tokens_per_s": round(lb.M / t, 1), "sequences_per_s": round(batch / t, 1)}
+        del lb
+    out.update(base)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(d, args.cpu_sample_tokens)
     print(json.dumps(out))

@@ -129,6 +129,17 @@ q8_status q8_linear(const int8_t* xq, const int8_t* wq, const float* bias,
                     uint32_t epilogue_flags, void* stream);
 
 /*
+ * The dynamic quantizer of Section 4.1 on its own: a = max|x| over the whole tensor, S = 127 / a (Eq. 3; 1.0 when
+ * a is 0), q = Quantize(x | S, 127) (Eq. 1) -- two launches (per-workgroup partial maxima, then a quantize pass
+ * that folds them), one for tensors of at most 16384 elements.  Same results as q8_absmax followed by q8_quantize.
+ *   x fp32[n]; q int8[n]; n >= 0 (n = 0: a = 0, S = 1).
+ *   scal_work fp32[Q8_SCAL_WORK], caller-provided scratch: on return scal_work[0] = a, scal_work[1] = S (a device
+ *   scalar to hand to q8_linear as sx); the rest holds the partial maxima.
+ *   zero_slot fp32[1] or NULL: set to 0 by the same launch (the out_amax of a q8_linear call that follows).
+ */
+q8_status q8_quantize_dynamic(const float* x, int64_t n, int8_t* q, float* scal_work, float* zero_slot, void* stream);
+
+/*
  * Dynamic-quantization FC layer in one call (Section 4.1): abs-max of x, S_x = 127/max,
  * quantize, then q8_linear.  Same results as calling the three entry points in turn.
  *   x fp32[M,K]; xq_work int8[M*K] and scal_work fp32[Q8_SCAL_WORK] are caller-provided
@@ -331,6 +342,18 @@ q8_status q8_attention(const float* qkv, int64_t B, int64_t S, int heads, int d,
  * while no other thread is inside q8_linear.  An unknown variant makes q8_linear return Q8_ERR_LAUNCH.
  */
 void q8_debug_set_gemm_variant(int variant);
+
+/*
+ * Measurement kernels for the benchmark: what the chip sustains next to the library's own kernels.
+ * q8_debug_mfma_rate: `workgroups` workgroups of 8 waves, every wave running iters x 8 independent
+ *   v_mfma_i32_32x32x32_i8 on operand fragments read once from `operands` (int8[65536], 16-byte aligned; their bit
+ *   pattern decides the clock the chip holds): 2 * 32*32*32 * 8 * iters * 8 * workgroups int8 operations, no
+ *   memory traffic.  sink int32[1] is never written in practice.
+ * q8_debug_stream_copy: dst[0..nbytes) = src[0..nbytes) with 16-byte accesses (src NULL: dst is filled instead);
+ *   nbytes a multiple of 16, pointers 16-byte aligned.
+ */
+q8_status q8_debug_mfma_rate(const int8_t* operands, int iters, int workgroups, int32_t* sink, void* stream);
+q8_status q8_debug_stream_copy(const void* src, void* dst, int64_t nbytes, void* stream);
 
 /* Library version string and a short text for a status code (host pointers, static storage). */
 const char* q8_version(void);

@@ -123,6 +123,24 @@ q8_status q8_linear(const int8_t* xq, const int8_t* wq, const float* bias, const
     return rc ? Q8_ERR_LAUNCH : Q8_OK;
 }
 
+q8_status q8_quantize_dynamic(const float* x, int64_t n, int8_t* q, float* scal_work, float* zero_slot, void* stream)
+{
+    if (n < 0) return Q8_ERR_SHAPE;
+    if (!scal_work) return Q8_ERR_NULL;
+    if (n > 0 && (!x || !q)) return Q8_ERR_NULL;
+    if (misaligned(x, 4) || misaligned(scal_work, 4) || misaligned(zero_slot, 4)) return Q8_ERR_ALIGN;
+    hipStream_t st = as_stream(stream);
+    if (n <= q8::quantize_onepass_max()) {
+        // a tensor one workgroup can hold in registers (an empty one included): abs-max, scale and quantize in a single launch
+        return q8::launch_quantize_onepass(x, n, scal_work, scal_work + 1, q, zero_slot, st) ? Q8_ERR_LAUNCH : Q8_OK;
+    }
+    // abs-max slots in scal_work[2..], folded by the quantize kernel: no atomics, no extra launch
+    int slots = 0;
+    if (q8::launch_absmax_partial(x, n, scal_work + 2, &slots, st)) return Q8_ERR_LAUNCH;
+    return q8::launch_quantize_amax(x, n, scal_work + 2, slots, scal_work, scal_work + 1, q, zero_slot, st) ? Q8_ERR_LAUNCH
+                                                                                                        : Q8_OK;
+}
+
 q8_status q8_linear_f32(const float* x, const int8_t* wq, const float* bias, const float* sw, int n_groups, int64_t M,
                         int64_t N, int64_t K, int8_t* xq_work, float* scal_work, void* y, int32_t* acc_out,
                         float* out_amax, const float* next_scale, uint32_t flags, void* stream)
@@ -134,23 +152,8 @@ q8_status q8_linear_f32(const float* x, const int8_t* wq, const float* bias, con
     if (s != Q8_OK) return s;
     if (M > 0 && K > 0 && (!x || !xq_work)) return Q8_ERR_NULL;
     if (misaligned(x, 4)) return Q8_ERR_ALIGN;
-    if (M * K == 0) {
-        s = q8_absmax(x, 0, scal_work, scal_work + 1, stream);
-        if (s != Q8_OK) return s;
-        if ((flags & Q8_EPI_ABSMAX) && q8::launch_absmax(x, 0, out_amax, nullptr, as_stream(stream))) return Q8_ERR_LAUNCH;
-    } else if (M * K <= q8::quantize_onepass_max()) {
-        // a tensor one workgroup can hold in registers: abs-max, scale and quantize in a single launch
-        if (q8::launch_quantize_onepass(x, M * K, scal_work, scal_work + 1, xq_work,
-                                        (flags & Q8_EPI_ABSMAX) ? out_amax : nullptr, as_stream(stream)))
-            return Q8_ERR_LAUNCH;
-    } else {
-        // abs-max slots in scal_work[2..], folded by the quantize kernel: no atomics, no extra launch
-        int slots = 0;
-        if (q8::launch_absmax_partial(x, M * K, scal_work + 2, &slots, as_stream(stream))) return Q8_ERR_LAUNCH;
-        if (q8::launch_quantize_amax(x, M * K, scal_work + 2, slots, scal_work, scal_work + 1, xq_work,
-                                     (flags & Q8_EPI_ABSMAX) ? out_amax : nullptr, as_stream(stream)))
-            return Q8_ERR_LAUNCH;
-    }
+    s = q8_quantize_dynamic(x, M * K, xq_work, scal_work, (flags & Q8_EPI_ABSMAX) ? out_amax : nullptr, stream);
+    if (s != Q8_OK) return s;
     return q8_linear(xq_work, wq, bias, scal_work + 1, sw, n_groups, M, N, K, y, acc_out, out_amax, next_scale, flags,
                      stream);
 }
@@ -343,6 +346,23 @@ const char* q8_status_str(q8_status s)
         case Q8_ERR_TOO_LARGE: return "input exceeds the static scratch of the no-allocation entry point";
     }
     return "unknown status";
+}
+
+q8_status q8_debug_mfma_rate(const int8_t* operands, int iters, int workgroups, int32_t* sink, void* stream)
+{
+    if (!operands || !sink) return Q8_ERR_NULL;
+    if (iters < 0 || workgroups < 1 || workgroups > 65536) return Q8_ERR_SHAPE;
+    if (misaligned(operands, 16) || misaligned(sink, 4)) return Q8_ERR_ALIGN;
+    return q8::launch_mfma_rate(operands, iters, workgroups, sink, as_stream(stream)) ? Q8_ERR_LAUNCH : Q8_OK;
+}
+
+q8_status q8_debug_stream_copy(const void* src, void* dst, int64_t nbytes, void* stream)
+{
+    if (nbytes < 0 || nbytes % 16) return Q8_ERR_SHAPE;
+    if (nbytes == 0) return Q8_OK;
+    if (!dst) return Q8_ERR_NULL;
+    if (misaligned(src, 16) || misaligned(dst, 16)) return Q8_ERR_ALIGN;
+    return q8::launch_stream_copy(src, dst, nbytes, as_stream(stream)) ? Q8_ERR_LAUNCH : Q8_OK;
 }
 
 /* Tuning hook for the benchmark (not part of the method): pick the MFMA tile variant, 0 = automatic. */

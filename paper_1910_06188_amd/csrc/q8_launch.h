@@ -73,6 +73,11 @@ int attention_generic_max_s();
 int launch_attention(const float* qkv, int64_t B, int64_t S, int heads, int d, const float* mask, float scale, float* ctx,
                      float* amax_slots, const float* q_scale, int8_t* q_out, hipStream_t st);
 
+// Measurement kernels of the benchmark (q8_ceiling.hip): a register-resident i8 MFMA loop on caller-given operands
+// (iters x 8 MFMAs per wave, 8 waves per workgroup) and a streaming copy (src null: fill) with 16-byte accesses.
+int launch_mfma_rate(const int8_t* ops, int iters, int workgroups, int* sink, hipStream_t st);
+int launch_stream_copy(const void* src, void* dst, int64_t nbytes, hipStream_t st);
+
 // Tuning hook used by the benchmark and tests: selects the MFMA tile variant
 // (0 = automatic choice from the shape).
 void set_gemm_variant(int v);

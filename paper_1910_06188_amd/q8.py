@@ -50,6 +50,12 @@ _lib.q8_embedding_sum3_layernorm.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _v
 _lib.q8_attention.argtypes = [_vp, _i64, _i64, _i32, _i32, _vp, _f32, _vp, _vp, _vp, _vp, _vp]
 _lib.q8_linear_f32_static.argtypes = [_vp, _vp, _vp, _vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _u32, _vp]
 _lib.q8_linear_f32_static.restype = C.c_int
+_lib.q8_quantize_dynamic.argtypes = [_vp, _i64, _vp, _vp, _vp, _vp]
+_lib.q8_quantize_dynamic.restype = C.c_int
+_lib.q8_debug_mfma_rate.argtypes = [_vp, _i32, _i32, _vp, _vp]
+_lib.q8_debug_mfma_rate.restype = C.c_int
+_lib.q8_debug_stream_copy.argtypes = [_vp, _vp, _i64, _vp]
+_lib.q8_debug_stream_copy.restype = C.c_int
 _lib.q8_linear_f32_slots.argtypes = [_vp, _vp, _i32, _vp, _vp, _vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _u32, _vp]
 for _f in ("q8_linear_f32_slots", "q8_attention", "q8_layernorm_absmax", "q8_embedding_sum3_layernorm", "q8_fake_quantize", "q8_ema_update", "q8_fake_quantize_ema", "q8_ste_backward", "q8_absmax", "q8_scale_from_amax", "q8_quantize", "q8_quantize_amax", "q8_linear", "q8_linear_f32", "q8_embedding",
            "q8_embedding_sum3"):
@@ -121,6 +127,28 @@ def q8_quantize_amax(x, amax, scale_out, q, amax_out=None, stream=None) -> None:
         raise ValueError("q8_quantize_amax: q and x differ in size")
     _ck(_lib.q8_quantize_amax(_ptr(x), x.numel(), _ptr(amax), amax.numel(), _ptr(amax_out), _ptr(scale_out), _ptr(q),
                               _stream(stream)), "q8_quantize_amax")
+
+
+def q8_quantize_dynamic(x, q, scal_work, zero_slot=None, stream=None) -> None:
+    """Dynamic quantizer (Section 4.1): scal_work[0] = max|x|, scal_work[1] = S = 127/max, q = Quantize(x | S, 127)."""
+    if q.numel() != x.numel() or scal_work.numel() < SCAL_WORK:
+        raise ValueError("q8_quantize_dynamic: shape mismatch")
+    _ck(_lib.q8_quantize_dynamic(_ptr(x), x.numel(), _ptr(q), _ptr(scal_work), _ptr(zero_slot), _stream(stream)),
+        "q8_quantize_dynamic")
+
+
+def debug_mfma_rate(operands, iters, workgroups, sink, stream=None) -> float:
+    """Launches the register-resident i8 MFMA loop; returns the int8 operations it performs."""
+    if operands.numel() < 65536:
+        raise ValueError("debug_mfma_rate: operands holds 65536 int8 values")
+    _ck(_lib.q8_debug_mfma_rate(_ptr(operands), int(iters), int(workgroups), _ptr(sink), _stream(stream)), "q8_debug_mfma_rate")
+    return 2.0 * 32 * 32 * 32 * 8 * iters * 8 * workgroups
+
+
+def debug_stream_copy(src, dst, stream=None) -> None:
+    """dst = src with 16-byte accesses (src None: fill)."""
+    nbytes = dst.numel() * dst.element_size()
+    _ck(_lib.q8_debug_stream_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)), "q8_debug_stream_copy")
 
 
 def q8_linear(xq, wq, bias, sx, sw, y, n_groups=1, acc_out=None, out_amax=None, next_scale=None, flags=0,

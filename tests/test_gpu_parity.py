@@ -676,6 +676,23 @@ def test_quantize_amax_one_value_and_partials(q8):
     np.testing.assert_array_equal(host(q)[1:14], O.quantize(x[1:14], 1.0))
 
 
+@pytest.mark.parametrize("n", [0, 1, 1000, 16384, 16385, 3_145_731])
+def test_quantize_dynamic_is_absmax_scale_quantize(q8, n):
+    """The dynamic quantizer of Section 4.1 in one call: max|x|, S = 127 / max (Eq. 3), codes by Eq. 1, all against the oracle;
+    the optional slot is cleared by the same launch."""
+    g = synth.rng(4900 + n % 97)
+    x = g.standard_normal(n, dtype=np.float32) * np.float32(3.0)
+    scal = torch.full((q8.SCAL_WORK,), -1.0, device="cuda")
+    q = torch.full((n,), 99, dtype=torch.int8, device="cuda")
+    slot = scalar(7.0)
+    q8.q8_quantize_dynamic(dev(x), q, scal, zero_slot=slot)
+    a = O.absmax(x) if n else np.float32(0.0)
+    s = O.scale(a)
+    assert host(scal)[0] == a and host(scal)[1] == s and host(slot)[0] == 0.0
+    if n:
+        np.testing.assert_array_equal(host(q), O.quantize(x, s))
+
+
 def test_linear_is_deterministic(q8):
     d = synth.fc_layer(48, 600, 512, 700)
     a = run_linear(q8, d["x"], d["W"], d["b"])
