@@ -62,7 +62,7 @@ __device__ __forceinline__ float dequant_factor(float sx, float sw)
 // log2 Q is smooth on [0, 6] (from -1 down to -29.9) and is fitted there by a degree-7
 // polynomial (least-squares Chebyshev fit of the exact function, see gelu_fit.py beside the
 // package; GELU error <= 5.3e-7 absolute, a fifth of the tolerance the tests allow); beyond
-// 6 the term is below 6e-9 and |v| is clamped.  Eleven VALU operations and one transcendental
+// 6 the term is below 6e-9 and |v| is clamped.  Ten VALU operations and one transcendental
 // per element: in the fused GEMM epilogue this arithmetic, not the store, is what the GELU
 // variants wait for.
 __device__ __forceinline__ float gelu_erf(float v)
@@ -75,7 +75,7 @@ __device__ __forceinline__ float gelu_erf(float v)
     p = __builtin_fmaf(p, a, -4.582974315e-01f);
     p = __builtin_fmaf(p, a, -1.151324630e+00f);
     p = __builtin_fmaf(p, a, -9.999869466e-01f);
-    return __builtin_fmaxf(v, 0.0f) - a * __builtin_amdgcn_exp2f(p);
+    return __builtin_fmaf(-a, __builtin_amdgcn_exp2f(p), __builtin_fmaxf(v, 0.0f));  // one rounding, one operation less
 }
 
 __device__ __forceinline__ unsigned wave_max_u32(unsigned v)

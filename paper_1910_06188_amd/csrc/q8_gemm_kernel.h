@@ -408,50 +408,10 @@ __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM*
             });
         });
         };
-        // 16-byte stores of int8 codes need y + row * N to stay 16-byte aligned
-        const bool y_rows_aligned = ((reinterpret_cast<uintptr_t>(ep.y) | (uintptr_t)N) & 15) == 0;
-        if ((kEpi == 4 || kEpi == 5) && y_rows_aligned) {
-            // Int8 output: one byte per lane and store instruction would put 16 x FM x FN partial-line stores per lane
-            // on the vector-memory path.  The codes go through LDS instead (the rings are dead by now): every lane
-            // drops its bytes into a row-major TM x TN staging tile of its own wave, and the wave reads the tile back
-            // 16 bytes per lane -- TN/16 lanes per row -- for 16-byte global stores: 16x fewer store instructions, row
-            // segments of TN bytes.  (A staging tile shared by the workgroup would give whole BN-byte rows per store, at
-            // the price of a second barrier; measured slower inside the layer step.)
-            constexpr int LPR = TN / 16, RPR = 64 / LPR;  // lanes per row, rows per 16-byte read
-            static_assert(TM % RPR == 0 && BM * BN <= LDS_BYTES, "staging tile");
-            typedef __attribute__((address_space(3))) v4i* lds_v4i_t;
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));  // the asm-issued (empty) ring loads of stages KT, KT+1 have landed
-            __syncthreads();                              // ... and every wave has left the rings
-            const lds_ptr_t stg = (lds_ptr_t)lds + wave * (TM * TN);
-            const lds_ptr_t my = stg + (4 * hi) * TN + l32;
-            static_for<0, FN>([&](auto jc) {
-                constexpr int j = decltype(jc)::value;
-                const ColConst cc = ColConst{ep.bias ? quantize_bias(bias_col[j], sx, sw_col[j]) : 0, dequant_factor(sx, sw_col[j])};
-                static_for<0, FM>([&](auto ic) {
-                    constexpr int i = decltype(ic)::value;
-                    static_for<0, 16>([&](auto ec) {
-                        constexpr int e = decltype(ec)::value;
-                        constexpr int dm = i * 32 + 8 * (e >> 2) + (e & 3);
-                        float yv = (float)(acc[i][j][e] + cc.bq) * cc.r;
-                        if (do_gelu) yv = gelu_erf(yv);
-                        my[dm * TN + j * 32] = (char)quantize_code(yv, next_scale);
-                    });
-                });
-            });
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // own bytes are in LDS (a wave's LDS operations complete in order)
-            const int rr = lane / LPR, cb = (lane % LPR) * 16;
-            const int vbase = (wm * TM + rr) * N + n0 + wn * TN + cb;
-            static_for<0, TM / RPR>([&](auto tc) {
-                constexpr int t = decltype(tc)::value;
-                const v4i v = *(lds_v4i_t)(stg + (t * RPR + rr) * TN + cb);
-                __builtin_amdgcn_raw_buffer_store_b128(v, ry, vbase + t * RPR * N, 0, 0);  // offsets in the VGPR only
-            });
-        } else {
         if (stream_out && !do_req)
             store_tile(std::true_type{});
         else
             store_tile(std::false_type{});
-        }
         amax = __float_as_uint(famax);  // non-negative floats order like their bit patterns
     } else {
         static_for<0, FN>([&](auto jc) {
