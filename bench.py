@@ -383,6 +383,25 @@ def main():
     layer.glue_once()
     M, H, F = layer.M, layer.H, layer.F
 
+    # What a HIP event pair adds to the kernel it brackets (the launch behind the first event waits for that event's
+    # marker, and the second event's marker waits for the kernel): pairs around one and around two launches of a
+    # one-thread kernel give t1 = o + k and t2 = o + 2k, so the overhead is o = 2 t1 - t2.  It is subtracted from every
+    # event-bracketed kernel time below; both the raw and the net figure are reported.
+    def event_overhead_us():
+        tiny_a, tiny_s = torch.ones(1, device="cuda"), torch.zeros(1, device="cuda")
+        res = []
+        for n in (1, 2):
+            pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(200)]
+            for a_, b_ in pairs:
+                layer.step()                         # the same surroundings as in the timed steps: a busy queue in front
+                a_.record()
+                for _ in range(n):
+                    q8.q8_scale_from_amax(tiny_a, tiny_s)
+                b_.record()
+            torch.cuda.synchronize()
+            res.append(float(np.median([a_.elapsed_time(b_) for a_, b_ in pairs])) * 1e3)
+        return max(0.0, 2.0 * res[0] - res[1])
+
     # ---- the timed region: K steps of the dynamic-quantization hot path -------------------------------------------------
     for _ in range(PREWARM_STEPS + args.warmup):
         layer.step()
@@ -408,7 +427,9 @@ def main():
     # bound by its HBM write; timed with events on the launch stream around that launch in every timed step
     shapes = {"qkv": ("fused QKV", 3 * H, H, 4), "attn_out": ("attention-output", H, H, 4),
               "ffn1": ("FFN1 + GELU + abs-max", F, H, 4), "ffn2": ("FFN2", H, F, 4)}
-    ffn1_us = float(np.mean([e["ffn1"][0].elapsed_time(e["ffn1"][1]) for e in evs])) * 1e3
+    ev_over = event_overhead_us()
+    ffn1_raw_us = float(np.mean([e["ffn1"][0].elapsed_time(e["ffn1"][1]) for e in evs])) * 1e3
+    ffn1_us = ffn1_raw_us - ev_over
     rb = gemm_bound(M, F, H, 4)
     ffn1_gbs = rb["bytes"] / (ffn1_us * 1e-6) / 1e9
     default_shape = (args.batch, args.seq) == (32, 384)
@@ -425,6 +446,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "gemm_mfma_kernel, FFN1 %dx%dx%d + GELU + abs-max, fp32 out (the step's longest kernel)" % (M, F, H),
                      "achieved": round(ffn1_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(ffn1_gbs / HBM_PEAK_GBS, 4), "avg_launch_us": round(ffn1_us, 2),
+                     "avg_event_pair_us": round(ffn1_raw_us, 2), "event_pair_overhead_us": round(ev_over, 2),
                      "algorithmic_bytes": rb["bytes"], "int8_tops": round(rb["ops"] / ffn1_us / 1e6, 1),
                      "pct_int8_mfma_peak": round(100.0 * rb["ops"] / ffn1_us / 1e6 / INT8_PEAK_TOPS, 2),
                      "traffic": profiled_traffic("FFN1_GELU_ABSMAX") if default_shape else None,
@@ -438,7 +460,7 @@ def main():
     torch.cuda.synchronize()
     per_gemm = {}
     for k, (label, N_, K_, ob) in shapes.items():
-        us = float(np.mean([e[k][0].elapsed_time(e[k][1]) for e in pevs])) * 1e3
+        us = float(np.mean([e[k][0].elapsed_time(e[k][1]) for e in pevs])) * 1e3 - ev_over
         b = gemm_bound(M, N_, K_, ob)
         per_gemm[label + " %dx%dx%d" % (M, N_, K_)] = {
             "us": round(us, 2), "bound": b["bound"], "bound_us": round(b["bound_us"], 2), "frac_of_roofline": round(b["bound_us"] / us, 4),
@@ -467,6 +489,17 @@ def main():
     ceil["hbm_stream_copy_201MB"] = {"us": round(us, 1), "GBps_read_plus_write": round(2.0 * nb / us / 1e3, 1), "frac_of_8TBps": round(2.0 * nb / us / 1e3 / HBM_PEAK_GBS, 3)}
     us = event_us(torch, lambda i: q8.debug_stream_copy(None, big[i % 5]), 20)
     ceil["hbm_stream_fill_201MB"] = {"us": round(us, 1), "GBps_write": round(nb / us / 1e3, 1), "frac_of_8TBps": round(nb / us / 1e3 / HBM_PEAK_GBS, 3)}
+    # one stage of a GEMM main loop (256 x 128 tile, 8 waves, 16 MFMAs per wave) piece by piece, zero operands: what the
+    # loop's structure costs when the 48 KiB of operand loads and the 16 KiB of fp32 stores of a K = 1024 tile share the
+    # compute unit's vector-memory path with it (64 KiB per stage = 64 B/clk at the matrix pipes' full rate)
+    opw, stw = torch.zeros(4 << 20, dtype=torch.int8, device="cuda"), torch.empty(8 << 20, device="cuda")
+    probe = {}
+    for what, label in ((0, "mfma_only"), (7, "plus_lds_reads_barrier_operand_loads"), (15, "plus_fp32_stores"),
+                        (64, "mfma_plus_gelu_arithmetic"), (71, "loads_and_gelu_arithmetic"), (79, "loads_gelu_and_stores")):
+        us = event_us(torch, lambda i, what=what: q8.debug_loop_probe(what, opw, stw, 2400, sink), 5, warm=2)
+        probe[label] = round(us * 1e3 / 2400, 1)
+    ceil["gemm_stage_probe_ns_per_stage"] = probe
+    del opw, stw
     out["measured_ceilings"] = ceil
     # The FFN2 launch on constant operands (every code 1): identical instruction stream and traffic, far fewer bits toggling
     # in the multipliers.  The gap to its per_gemm figure is the chip's power management, not the kernel's structure.

@@ -354,6 +354,16 @@ void q8_debug_set_gemm_variant(int variant);
  */
 q8_status q8_debug_mfma_rate(const int8_t* operands, int iters, int workgroups, int32_t* sink, void* stream);
 q8_status q8_debug_stream_copy(const void* src, void* dst, int64_t nbytes, void* stream);
+/*
+ * q8_debug_loop_probe: one stage of a GEMM main loop, piece by piece -- 256 workgroups of 8 waves run `stages` stages of 16
+ * MFMAs per wave (a 256 x 128 tile in 128-byte K stages) on zero operands, plus what `what` adds (a sum of: 1 the
+ * fragment reads from LDS, 2 the stage barrier, 4 the stage's 48 KiB of global -> LDS loads, 8 eight dword stores per
+ * wave -- 16 KiB per workgroup, the fp32 output of a K = 1024 tile spread over its stages --, 64 eight GELU evaluations
+ * per wave; accepted: 0, 7, 15, 64, 71, 79).  Shows which part of a kernel's structure costs what, with the clock
+ * unaffected by operand toggling.  operand_window: 4 MiB to load from; store_window: 32 MiB to store into (both
+ * device, 16-byte aligned, contents irrelevant).
+ */
+q8_status q8_debug_loop_probe(int what, const void* operand_window, float* store_window, int stages, int32_t* sink, void* stream);
 
 /* Library version string and a short text for a status code (host pointers, static storage). */
 const char* q8_version(void);

@@ -356,6 +356,15 @@ q8_status q8_debug_mfma_rate(const int8_t* operands, int iters, int workgroups, 
     return q8::launch_mfma_rate(operands, iters, workgroups, sink, as_stream(stream)) ? Q8_ERR_LAUNCH : Q8_OK;
 }
 
+q8_status q8_debug_loop_probe(int what, const void* operand_window, float* store_window, int stages, int32_t* sink, void* stream)
+{
+    if (!operand_window || !store_window || !sink) return Q8_ERR_NULL;
+    if (stages < 0 || stages > (1 << 24)) return Q8_ERR_SHAPE;
+    if (misaligned(operand_window, 16) || misaligned(store_window, 16) || misaligned(sink, 4)) return Q8_ERR_ALIGN;
+    if (what != 0 && what != 7 && what != 15 && what != 64 && what != 71 && what != 79) return Q8_ERR_FLAGS;
+    return q8::launch_loop_probe(what, operand_window, store_window, stages, sink, as_stream(stream)) ? Q8_ERR_LAUNCH : Q8_OK;
+}
+
 q8_status q8_debug_stream_copy(const void* src, void* dst, int64_t nbytes, void* stream)
 {
     if (nbytes < 0 || nbytes % 16) return Q8_ERR_SHAPE;

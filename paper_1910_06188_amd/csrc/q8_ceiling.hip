@@ -3,6 +3,8 @@
 //   - a register-resident loop of v_mfma_i32_32x32x32_i8 on caller-given int8 operands: the matrix pipes' own
 //     ceiling on that data (operand bit toggling moves the clock the power management allows);
 //   - a streaming copy and a streaming fill with 16-byte accesses: what the HBM sustains.
+#include <type_traits>
+
 #include "q8_device.h"
 #include "q8_launch.h"
 
@@ -46,6 +48,150 @@ __global__ __launch_bounds__(256) void stream_fill_kernel(float4* __restrict__ d
     const int64_t stride = (int64_t)gridDim.x * 256;
     const float4 f = make_float4(v, v, v, v);
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = f;
+}
+
+// One stage of a GEMM main loop, piece by piece: 8 waves, 4 accumulator blocks per wave, 16 MFMAs per wave and stage
+// (a 256 x 128 tile walked in 128-byte stages), optionally with what a real kernel adds around them.  kWhat bits:
+//   1  fragment reads from LDS (16 ds_read_b128 per wave and stage, swizzled rows as in the GEMM)
+//   2  the stage barrier
+//   4  global -> LDS loads of a stage (6 x 1 KiB per wave = 48 KiB per workgroup) from a 1 MiB window that stays in L2
+//   8  8 dword stores per wave and stage (16 KiB per workgroup: the fp32 output of a K = 1024 tile spread over its stages)
+//   64 8 GELU-sized vector-ALU chains per wave and stage (the fused epilogue's arithmetic)
+// LDS holds zeros, so the clock is not lowered by operand toggling: the figures isolate the structure.  Everything is
+// addressed through buffer descriptors sized to the caller's buffers.
+template <int I, int E, class F>
+__device__ __forceinline__ void probe_for(F&& f)
+{
+    if constexpr (I < E) {
+        f(std::integral_constant<int, I>{});
+        probe_for<I + 1, E>(f);
+    }
+}
+
+template <int kWhat>
+__global__ __launch_bounds__(512, 2) void loop_probe_kernel(const char* opbuf, float* ybuf, int stages, int* sink)
+{
+    constexpr int kStage = 49152;
+    __shared__ __attribute__((aligned(1024))) char lds[3 * kStage];
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned long long p = reinterpret_cast<unsigned long long>(opbuf);
+    v4i rs;
+    rs[0] = (int)(p & 0xffffffffu), rs[1] = (int)((p >> 32) & 0xffff), rs[2] = (int)(4u << 20), rs[3] = 0x00020000;
+    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds;
+    for (int i = threadIdx.x; i < 3 * kStage / 4; i += 512) reinterpret_cast<int*>(lds)[i] = 0;
+    __syncthreads();
+    v16i acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0;
+    v4i fa[2][2], fb[2][2];
+    const int l32 = lane & 31, hi = lane >> 5, wm = wave / 2, wn = wave % 2;
+    int a_frag[2][4], b_frag[2][4];
+#pragma unroll
+    for (int f = 0; f < 2; ++f)
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const int ra = wm * 64 + f * 32 + l32, rb = wn * 64 + f * 32 + l32;
+            a_frag[f][ks] = ra * 128 + (((ks * 2 + hi) ^ ((ra ^ (ra >> 3)) & 7)) << 4);
+            b_frag[f][ks] = 32768 + rb * 128 + (((ks * 2 + hi) ^ ((rb ^ (rb >> 3)) & 7)) << 4);
+        }
+#pragma unroll
+    for (int f = 0; f < 2; ++f) {
+        fa[0][f] = *reinterpret_cast<const v4i*>(lds + a_frag[f][0]);
+        fb[0][f] = *reinterpret_cast<const v4i*>(lds + b_frag[f][0]);
+        fa[1][f] = fa[0][f];
+        fb[1][f] = fb[0][f];
+    }
+    const unsigned voff = (unsigned)((blockIdx.x * 8192 + threadIdx.x * 16) % (1u << 20));  // + at most 5 * 8192 + 16 < 4 MiB
+    int slot = 0;
+    float fsink = 0.f;
+    int hold[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) hold[i] = (int)(threadIdx.x * 37 + i * 1001);
+    const __amdgpu_buffer_rsrc_t ry =
+        __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<char*>(ybuf) + (size_t)blockIdx.x * 131072, 0, 131072, 0x00020000);
+    for (int st = 0; st < stages; ++st) {
+        const unsigned ybase = (unsigned)(((st * 8 + wave) % 64) * 2048);  // + 7 * 256 + 63 * 4 + 4 <= 131072
+        const int slot_next = slot == 2 ? 0 : slot + 1, slot_load = slot == 0 ? 2 : slot - 1;
+        const char* cur_s = lds + slot * kStage;
+        const char* nxt_s = lds + slot_next * kStage;
+        probe_for<0, 4>([&](auto ksc) {
+            constexpr int ks = decltype(ksc)::value;
+            constexpr int C = ks & 1, Nx = (ks + 1) & 1;
+            if constexpr (ks == 3) {
+                if constexpr ((kWhat & 4) != 0)
+                    asm volatile("s_waitcnt vmcnt(6) lgkmcnt(0)" ::: "memory");
+                else if constexpr ((kWhat & 1) != 0)
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                if constexpr ((kWhat & 2) != 0) {
+                    asm volatile("" ::: "memory");
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            probe_for<0, 4>([&](auto mc) {
+                constexpr int idx = decltype(mc)::value;
+                constexpr int i = idx / 2, j = idx % 2;
+                acc[idx] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[C][i], fb[C][j], acc[idx], 0, 0, 0);
+                if constexpr ((kWhat & 1) != 0 && idx == 0) {
+                    const char* b = ks == 3 ? nxt_s : cur_s;
+                    constexpr int ksn = ks == 3 ? 0 : ks + 1;
+                    constexpr int nb = ks == 3 ? 0 : Nx;
+                    fa[nb][0] = *reinterpret_cast<const v4i*>(b + a_frag[0][ksn]);
+                    fa[nb][1] = *reinterpret_cast<const v4i*>(b + a_frag[1][ksn]);
+                    fb[nb][0] = *reinterpret_cast<const v4i*>(b + b_frag[0][ksn]);
+                    fb[nb][1] = *reinterpret_cast<const v4i*>(b + b_frag[1][ksn]);
+                }
+                if constexpr ((kWhat & 4) != 0 && ks < 3 && (idx & 1) != 0) {
+                    constexpr int l = ks * 2 + idx / 2;  // LDS target: slot + wave * 6 KiB + l KiB + 16 * lane < 3 * kStage
+                    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                                 :
+                                 : "s"(lds_base + (unsigned)(slot_load * kStage + wave * 6144 + l * 1024)), "v"(voff), "s"(rs),
+                                   "s"((unsigned)(l * 8192))
+                                 : "memory");
+                }
+                if constexpr ((kWhat & 64) != 0 && (idx & 1) != 0) {
+                    constexpr int q = ks * 2 + idx / 2;
+                    hold[q] ^= st;
+                    const float v = gelu_erf((float)hold[q] * 1.0e-3f);
+                    fsink = __builtin_fmaxf(fsink, __builtin_fabsf(v));
+                    if constexpr ((kWhat & 8) != 0) __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), ry, ybase + q * 256 + lane * 4, 0, 2);
+                } else if constexpr ((kWhat & 8) != 0 && (idx & 1) != 0) {
+                    constexpr int q = ks * 2 + idx / 2;
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint((float)acc[idx][q]), ry, ybase + q * 256 + lane * 4, 0, 2);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        });
+        slot = slot_next;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s ^= acc[i][e];
+    if ((s == 0x7fffffff && stages < 0) || fsink == 1.2345f) sink[0] = s;
+}
+
+int launch_loop_probe(int what, const void* opbuf, float* ybuf, int stages, int* sink, hipStream_t st)
+{
+    const char* ob = reinterpret_cast<const char*>(opbuf);
+#define Q8_PROBE(W) \
+    case W: hipLaunchKernelGGL(loop_probe_kernel<W>, dim3(256), dim3(512), 0, st, ob, ybuf, stages, sink); break
+    switch (what) {
+        Q8_PROBE(0);
+        Q8_PROBE(7);
+        Q8_PROBE(15);
+        Q8_PROBE(64);
+        Q8_PROBE(71);
+        Q8_PROBE(79);
+        default: return 1;
+    }
+#undef Q8_PROBE
+    return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
 int launch_mfma_rate(const int8_t* ops, int iters, int workgroups, int* sink, hipStream_t st)

@@ -77,6 +77,8 @@ int launch_attention(const float* qkv, int64_t B, int64_t S, int heads, int d, c
 // (iters x 8 MFMAs per wave, 8 waves per workgroup) and a streaming copy (src null: fill) with 16-byte accesses.
 int launch_mfma_rate(const int8_t* ops, int iters, int workgroups, int* sink, hipStream_t st);
 int launch_stream_copy(const void* src, void* dst, int64_t nbytes, hipStream_t st);
+// One stage of a GEMM main loop piece by piece (what: 0, 7, 15, 64, 71 or 79; see q8_ceiling.hip): 256 workgroups x `stages` stages.
+int launch_loop_probe(int what, const void* opbuf, float* ybuf, int stages, int* sink, hipStream_t st);
 
 // Tuning hook used by the benchmark and tests: selects the MFMA tile variant
 // (0 = automatic choice from the shape).

@@ -16,6 +16,8 @@ namespace q8 {
 
 constexpr int kLnThreads = 256;            // four waves = four rows per workgroup per trip
 constexpr int kLnMaxVec = 8;               // float4 vectors per lane: rows up to 64 * 4 * 8 = 2048 columns
+constexpr int kLnRowsShort = 2;           // rows a wave carries side by side: plain LayerNorm of rows of at most 1024 columns (with a
+                                          // residual or the embedding rows in front the extra registers cost more than they win)
 constexpr int kLnSlots = 2048;             // abs-max slots (= Q8_AMAX_SLOTS): one per workgroup, the rest zero
 
 __device__ __forceinline__ double wave_sum_f64(double v)
@@ -55,8 +57,9 @@ __device__ __forceinline__ float4 dequant4_ln(unsigned packed, float r)
 
 // kSrc: 0 = x is a; 1 = x is a + r (one binary32 addition); 2 = x is the sum of three
 // dequantized embedding rows, (word + position) + type as in the plain lookup.
-// H % 4 == 0, H <= 2048, every pointer 16-byte aligned (tables 4-byte).
-template <int kSrc>
+// H % 4 == 0, H <= 256 * kVec (kVec float4 vectors per lane: 4 for rows of up to 1024 columns -- fewer registers, more
+// waves in flight -- 8 up to 2048), every pointer 16-byte aligned (tables 4-byte).
+template <int kSrc, int kVec, int kRows>
 __global__ __launch_bounds__(kLnThreads) void layernorm_rows_kernel(const float* a, const float* r, EmbedSrc es,
                                                                      const float* __restrict__ gamma,
                                                                      const float* __restrict__ beta, double eps,
@@ -76,74 +79,100 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_rows_kernel(const float*
         r1 = __fdiv_rn(1.0f, es.scales[1]);
         r2 = __fdiv_rn(1.0f, es.scales[2]);
     }
-    for (int64_t row = ((int64_t)blockIdx.x * (kLnThreads / 64)) + wave; row < M;
-         row += (int64_t)gridDim.x * (kLnThreads / 64)) {
-        float4 x[kLnMaxVec];
-        if (kSrc == 2) {
-            const int64_t ia = es.wid[row], ib = es.pid[row], ic = es.tid[row];
-            const bool ok = ia >= 0 && ia < es.Vw && ib >= 0 && ib < es.Vp && ic >= 0 && ic < es.Vt;
-            if (!ok && es.err_flag && lane == 0) es.err_flag[0] = 1;
-            const unsigned* wr = es.word + (ok ? ia : 0) * nvec;
-            const unsigned* pr = es.pos + (ok ? ib : 0) * nvec;
-            const unsigned* tr = es.typ + (ok ? ic : 0) * nvec;
+    // A wave takes kRows consecutive rows per trip and carries them side by side: all their loads are in flight
+    // together and their reductions -- chains of dependent cross-lane exchanges -- interleave, so a wave spends its
+    // time waiting for memory once per trip instead of once per row.  Each row's arithmetic is unchanged.
+    constexpr int kWaves = kLnThreads / 64;
+    for (int64_t row0 = ((int64_t)blockIdx.x * kWaves + wave) * kRows; row0 < M; row0 += (int64_t)gridDim.x * kWaves * kRows) {
+        float4 x[kRows][kVec];
+        bool live[kRows];
 #pragma unroll
-            for (int j = 0; j < kLnMaxVec; ++j) {
-                const int v = j * 64 + lane;
-                x[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (v < nvec && ok) {
-                    const float4 p = dequant4_ln(wr[v], r0), q = dequant4_ln(pr[v], r1), t = dequant4_ln(tr[v], r2);
-                    x[j] = make_float4((p.x + q.x) + t.x, (p.y + q.y) + t.y, (p.z + q.z) + t.z, (p.w + q.w) + t.w);
+        for (int q = 0; q < kRows; ++q) {
+            const int64_t row = row0 + q;
+            live[q] = row < M;
+#pragma unroll
+            for (int j = 0; j < kVec; ++j) x[q][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (!live[q]) continue;
+            if (kSrc == 2) {
+                const int64_t ia = es.wid[row], ib = es.pid[row], ic = es.tid[row];
+                const bool ok = ia >= 0 && ia < es.Vw && ib >= 0 && ib < es.Vp && ic >= 0 && ic < es.Vt;
+                if (!ok && es.err_flag && lane == 0) es.err_flag[0] = 1;
+                const unsigned* wr = es.word + (ok ? ia : 0) * nvec;
+                const unsigned* pr = es.pos + (ok ? ib : 0) * nvec;
+                const unsigned* tr = es.typ + (ok ? ic : 0) * nvec;
+#pragma unroll
+                for (int j = 0; j < kVec; ++j) {
+                    const int v = j * 64 + lane;
+                    if (v < nvec && ok) {
+                        const float4 p = dequant4_ln(wr[v], r0), t1 = dequant4_ln(pr[v], r1), t2 = dequant4_ln(tr[v], r2);
+                        x[q][j] = make_float4((p.x + t1.x) + t2.x, (p.y + t1.y) + t2.y, (p.z + t1.z) + t2.z, (p.w + t1.w) + t2.w);
+                    }
                 }
-            }
-        } else {
-            const float4* av = reinterpret_cast<const float4*>(a) + row * nvec;
-            const float4* rv = kSrc == 1 ? reinterpret_cast<const float4*>(r) + row * nvec : nullptr;
+            } else {
+                const float4* av = reinterpret_cast<const float4*>(a) + row * nvec;
+                const float4* rv = kSrc == 1 ? reinterpret_cast<const float4*>(r) + row * nvec : nullptr;
 #pragma unroll
-            for (int j = 0; j < kLnMaxVec; ++j) {
-                const int v = j * 64 + lane;
-                x[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (v < nvec) {
-                    x[j] = load_f4_nt_ln(&av[v]);
-                    if (kSrc == 1) {
-                        const float4 q = load_f4_nt_ln(&rv[v]);
-                        x[j] = make_float4(__fadd_rn(x[j].x, q.x), __fadd_rn(x[j].y, q.y), __fadd_rn(x[j].z, q.z),
-                                           __fadd_rn(x[j].w, q.w));
+                for (int j = 0; j < kVec; ++j) {
+                    const int v = j * 64 + lane;
+                    if (v < nvec) {
+                        x[q][j] = load_f4_nt_ln(&av[v]);
+                        if (kSrc == 1) {
+                            const float4 t = load_f4_nt_ln(&rv[v]);
+                            x[q][j] = make_float4(__fadd_rn(x[q][j].x, t.x), __fadd_rn(x[q][j].y, t.y), __fadd_rn(x[q][j].z, t.z),
+                                                  __fadd_rn(x[q][j].w, t.w));
+                        }
                     }
                 }
             }
         }
-        double s = 0.0;
+        double mean[kRows], rstd[kRows];
 #pragma unroll
-        for (int j = 0; j < kLnMaxVec; ++j)  // lanes past the row hold zeros
-            s += ((double)x[j].x + (double)x[j].y) + ((double)x[j].z + (double)x[j].w);
-        const double mean = wave_sum_f64(s) / (double)H;
-        double ss = 0.0;
+        for (int q = 0; q < kRows; ++q) {
+            double s = 0.0;
 #pragma unroll
-        for (int j = 0; j < kLnMaxVec; ++j) {
-            if (j * 64 + lane < nvec) {
-                const double d0 = (double)x[j].x - mean, d1 = (double)x[j].y - mean;
-                const double d2 = (double)x[j].z - mean, d3 = (double)x[j].w - mean;
-                ss += (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
-            }
+            for (int j = 0; j < kVec; ++j)  // lanes past the row hold zeros
+                s += ((double)x[q][j].x + (double)x[q][j].y) + ((double)x[q][j].z + (double)x[q][j].w);
+            mean[q] = s;
         }
-        const double rstd = 1.0 / sqrt(wave_sum_f64(ss) / (double)H + eps);
-        float4* yv = reinterpret_cast<float4*>(y) + row * nvec;
 #pragma unroll
-        for (int j = 0; j < kLnMaxVec; ++j) {
-            const int v = j * 64 + lane;
-            if (v < nvec) {
-                const float4 g = reinterpret_cast<const float4*>(gamma)[v], b = reinterpret_cast<const float4*>(beta)[v];
-                float4 o;
-                o.x = (float)(((double)x[j].x - mean) * rstd * (double)g.x + (double)b.x);
-                o.y = (float)(((double)x[j].y - mean) * rstd * (double)g.y + (double)b.y);
-                o.z = (float)(((double)x[j].z - mean) * rstd * (double)g.z + (double)b.z);
-                o.w = (float)(((double)x[j].w - mean) * rstd * (double)g.w + (double)b.w);
-                yv[v] = o;
-                if (q_out)  // stored-scale quantizer of the next FC (Eq. 1 on the rounded fp32 value), 4 codes per lane
-                    q_out[row * nvec + v] = ((unsigned)quantize_code(o.x, qs) & 0xffu) | (((unsigned)quantize_code(o.y, qs) & 0xffu) << 8) |
-                                            (((unsigned)quantize_code(o.z, qs) & 0xffu) << 16) | ((unsigned)quantize_code(o.w, qs) << 24);
-                amax = __builtin_fmaxf(amax, __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(o.x), __builtin_fabsf(o.y)),
-                                                            __builtin_fmaxf(__builtin_fabsf(o.z), __builtin_fabsf(o.w))));
+        for (int q = 0; q < kRows; ++q) mean[q] = wave_sum_f64(mean[q]) / (double)H;
+#pragma unroll
+        for (int q = 0; q < kRows; ++q) {
+            double ss = 0.0;
+#pragma unroll
+            for (int j = 0; j < kVec; ++j) {
+                if (j * 64 + lane < nvec) {
+                    const double d0 = (double)x[q][j].x - mean[q], d1 = (double)x[q][j].y - mean[q];
+                    const double d2 = (double)x[q][j].z - mean[q], d3 = (double)x[q][j].w - mean[q];
+                    ss += (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
+                }
+            }
+            rstd[q] = ss;
+        }
+#pragma unroll
+        for (int q = 0; q < kRows; ++q) rstd[q] = 1.0 / sqrt(wave_sum_f64(rstd[q]) / (double)H + eps);
+#pragma unroll
+        for (int q = 0; q < kRows; ++q) {
+            if (!live[q]) continue;
+            const int64_t row = row0 + q;
+            float4* yv = reinterpret_cast<float4*>(y) + row * nvec;
+#pragma unroll
+            for (int j = 0; j < kVec; ++j) {
+                const int v = j * 64 + lane;
+                if (v < nvec) {
+                    const float4 g = reinterpret_cast<const float4*>(gamma)[v], b = reinterpret_cast<const float4*>(beta)[v];
+                    float4 o;
+                    o.x = (float)(((double)x[q][j].x - mean[q]) * rstd[q] * (double)g.x + (double)b.x);
+                    o.y = (float)(((double)x[q][j].y - mean[q]) * rstd[q] * (double)g.y + (double)b.y);
+                    o.z = (float)(((double)x[q][j].z - mean[q]) * rstd[q] * (double)g.z + (double)b.z);
+                    o.w = (float)(((double)x[q][j].w - mean[q]) * rstd[q] * (double)g.w + (double)b.w);
+                    yv[v] = o;
+                    if (q_out)  // stored-scale quantizer of the next FC (Eq. 1 on the rounded fp32 value), 4 codes per lane
+                        q_out[row * nvec + v] = ((unsigned)quantize_code(o.x, qs) & 0xffu) | (((unsigned)quantize_code(o.y, qs) & 0xffu) << 8) |
+                                                (((unsigned)quantize_code(o.z, qs) & 0xffu) << 16) | ((unsigned)quantize_code(o.w, qs) << 24);
+                    amax = __builtin_fmaxf(amax, __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(o.x), __builtin_fabsf(o.y)),
+                                                                __builtin_fmaxf(__builtin_fabsf(o.z), __builtin_fabsf(o.w))));
+                }
             }
         }
     }
@@ -240,10 +269,11 @@ __global__ void amax_slots_clear_kernel(unsigned* slots)
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-static int ln_grid(int64_t M)
+static int ln_grid(int64_t M, int rows_per_wave = 1)
 {
     // one slot per workgroup caps the grid; within the cap, spread the rows evenly over the trips
-    const int64_t need = (M + kLnThreads / 64 - 1) / (kLnThreads / 64);
+    const int64_t per_wg = (int64_t)(kLnThreads / 64) * rows_per_wave;
+    const int64_t need = (M + per_wg - 1) / per_wg;
     if (need <= 1) return 1;
     const int64_t trips = (need + kLnSlots - 1) / kLnSlots;
     return (int)((need + trips - 1) / trips);
@@ -263,10 +293,18 @@ int launch_layernorm(const float* a, const float* r, const float* gamma, const f
     const dim3 grid(ln_grid(M)), block(kLnThreads);
     if (fast) {
         if (r)
-            hipLaunchKernelGGL(layernorm_rows_kernel<1>, grid, block, 0, st, a, r, es, gamma, beta, (double)eps, M,
+            if (H <= 1024)
+                hipLaunchKernelGGL((layernorm_rows_kernel<1, 4, 1>), dim3(ln_grid(M, 1)), block, 0, st, a, r, es, gamma, beta, (double)eps, M,
+                               (int)H, y, slots, q_scale, reinterpret_cast<unsigned*>(q_out));
+            else
+                hipLaunchKernelGGL((layernorm_rows_kernel<1, 8, 1>), grid, block, 0, st, a, r, es, gamma, beta, (double)eps, M,
                                (int)H, y, slots, q_scale, reinterpret_cast<unsigned*>(q_out));
         else
-            hipLaunchKernelGGL(layernorm_rows_kernel<0>, grid, block, 0, st, a, r, es, gamma, beta, (double)eps, M,
+            if (H <= 1024)
+                hipLaunchKernelGGL((layernorm_rows_kernel<0, 4, kLnRowsShort>), dim3(ln_grid(M, kLnRowsShort)), block, 0, st, a, r, es, gamma, beta, (double)eps, M,
+                               (int)H, y, slots, q_scale, reinterpret_cast<unsigned*>(q_out));
+            else
+                hipLaunchKernelGGL((layernorm_rows_kernel<0, 8, 1>), grid, block, 0, st, a, r, es, gamma, beta, (double)eps, M,
                                (int)H, y, slots, q_scale, reinterpret_cast<unsigned*>(q_out));
     } else {
         if (r)
@@ -303,7 +341,11 @@ int launch_embedding_sum3_layernorm(const int8_t* word, int64_t Vw, const int8_t
                       aligned16(gamma) && aligned16(beta) && a4(q_out);
     const dim3 grid(ln_grid(T)), block(kLnThreads);
     if (fast)
-        hipLaunchKernelGGL(layernorm_rows_kernel<2>, grid, block, 0, st, nullptr, nullptr, es, gamma, beta,
+        if (H <= 1024)
+                hipLaunchKernelGGL((layernorm_rows_kernel<2, 4, 1>), dim3(ln_grid(T, 1)), block, 0, st, nullptr, nullptr, es, gamma, beta,
+                           (double)eps, T, (int)H, y, slots, q_scale, reinterpret_cast<unsigned*>(q_out));
+            else
+                hipLaunchKernelGGL((layernorm_rows_kernel<2, 8, 1>), grid, block, 0, st, nullptr, nullptr, es, gamma, beta,
                            (double)eps, T, (int)H, y, slots, q_scale, reinterpret_cast<unsigned*>(q_out));
     else
         hipLaunchKernelGGL(layernorm_generic_kernel<2>, grid, block, 0, st, nullptr, nullptr, es, word, pos, typ, gamma,

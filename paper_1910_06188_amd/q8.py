@@ -56,6 +56,8 @@ _lib.q8_debug_mfma_rate.argtypes = [_vp, _i32, _i32, _vp, _vp]
 _lib.q8_debug_mfma_rate.restype = C.c_int
 _lib.q8_debug_stream_copy.argtypes = [_vp, _vp, _i64, _vp]
 _lib.q8_debug_stream_copy.restype = C.c_int
+_lib.q8_debug_loop_probe.argtypes = [_i32, _vp, _vp, _i32, _vp, _vp]
+_lib.q8_debug_loop_probe.restype = C.c_int
 _lib.q8_linear_f32_slots.argtypes = [_vp, _vp, _i32, _vp, _vp, _vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _u32, _vp]
 for _f in ("q8_linear_f32_slots", "q8_attention", "q8_layernorm_absmax", "q8_embedding_sum3_layernorm", "q8_fake_quantize", "q8_ema_update", "q8_fake_quantize_ema", "q8_ste_backward", "q8_absmax", "q8_scale_from_amax", "q8_quantize", "q8_quantize_amax", "q8_linear", "q8_linear_f32", "q8_embedding",
            "q8_embedding_sum3"):
@@ -149,6 +151,14 @@ def debug_stream_copy(src, dst, stream=None) -> None:
     """dst = src with 16-byte accesses (src None: fill)."""
     nbytes = dst.numel() * dst.element_size()
     _ck(_lib.q8_debug_stream_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)), "q8_debug_stream_copy")
+
+
+def debug_loop_probe(what, operand_window, store_window, stages, sink, stream=None) -> None:
+    """One stage of a GEMM main loop piece by piece (see include/q8.h); 256 workgroups x `stages` stages."""
+    if operand_window.numel() * operand_window.element_size() < (4 << 20) or store_window.numel() * store_window.element_size() < (32 << 20):
+        raise ValueError("debug_loop_probe: windows of 4 MiB and 32 MiB")
+    _ck(_lib.q8_debug_loop_probe(int(what), _ptr(operand_window), _ptr(store_window), int(stages), _ptr(sink), _stream(stream)),
+        "q8_debug_loop_probe")
 
 
 def q8_linear(xq, wq, bias, sx, sw, y, n_groups=1, acc_out=None, out_amax=None, next_scale=None, flags=0,
