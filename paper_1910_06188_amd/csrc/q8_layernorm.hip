@@ -20,11 +20,28 @@ constexpr int kLnRowsShort = 2;           // rows a wave carries side by side: p
                                           // residual or the embedding rows in front the extra registers cost more than they win)
 constexpr int kLnSlots = 2048;             // abs-max slots (= Q8_AMAX_SLOTS): one per workgroup, the rest zero
 
+// Sum of a double over the 64 lanes, the same value in every lane, in a fixed order (so the same bytes come out on
+// every run): an inclusive scan inside each row of 16 lanes with DPP row shifts (1, 2, 4, 8; lanes shifted in from
+// outside the row contribute zero), then the row totals carried across rows with the two row broadcasts, and lane
+// 63's total read back as a scalar.  A 64-bit value moves as two 32-bit DPP moves; the cross-lane traffic stays in
+// the vector ALU (a butterfly of ds_bpermute exchanges costs ten times the latency, and a wave does two of these
+// reductions per row with nothing else to do meanwhile).
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ double dpp_move_f64(double v)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), kCtrl, kRowMask, 0xf, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), kCtrl, kRowMask, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
 __device__ __forceinline__ double wave_sum_f64(double v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
+    v += dpp_move_f64<0x111, 0xf>(v);  // row_shr:1
+    v += dpp_move_f64<0x112, 0xf>(v);  // row_shr:2
+    v += dpp_move_f64<0x114, 0xf>(v);  // row_shr:4
+    v += dpp_move_f64<0x118, 0xf>(v);  // row_shr:8   -> lane 15 of each row holds its row's sum
+    v += dpp_move_f64<0x142, 0xa>(v);  // row_bcast:15 into rows 1 and 3
+    v += dpp_move_f64<0x143, 0xc>(v);  // row_bcast:31 into rows 2 and 3 -> lane 63 holds the total
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), 63), __builtin_amdgcn_readlane(__double2loint(v), 63));
 }
 
 // 16-byte load with the non-temporal hint: the inputs of a LayerNorm are read exactly once, and streamed

@@ -119,6 +119,24 @@ def test_host_side_argument_checks(lib):
     assert lib.q8_linear_f32_static(p, p, None, p, 1, (64 << 20) // 1024 + 1, 8, 1024, p, None, None, None, 0, None) == TOO_LARGE
     assert lib.q8_linear_f32_static(p, p, None, p, 1, -1, 8, 1024, p, None, None, None, 0, None) == SHAPE
     assert lib.q8_linear_f32_static(p, p, None, p, 1, 4, 8, 128, p, p + 2, None, None, 0, None) == ALIGN
+    # the dynamic quantizer on its own, and the measurement kernels' argument checks
+    lib.q8_quantize_dynamic.argtypes = [vp, i64, vp, vp, vp, vp]
+    assert lib.q8_quantize_dynamic(p, -1, p, p, None, None) == SHAPE
+    assert lib.q8_quantize_dynamic(p, 8, p, None, None, None) == NULL
+    assert lib.q8_quantize_dynamic(None, 8, p, p, None, None) == NULL
+    assert lib.q8_quantize_dynamic(p + 2, 8, p, p, None, None) == ALIGN
+    lib.q8_debug_mfma_rate.argtypes = [vp, C.c_int, C.c_int, vp, vp]
+    lib.q8_debug_stream_copy.argtypes = [vp, vp, i64, vp]
+    lib.q8_debug_loop_probe.argtypes = [C.c_int, vp, vp, C.c_int, vp, vp]
+    assert lib.q8_debug_mfma_rate(None, 1, 1, p, None) == NULL
+    assert lib.q8_debug_mfma_rate(p, -1, 1, p, None) == SHAPE
+    assert lib.q8_debug_mfma_rate(p + 4, 1, 1, p, None) == ALIGN
+    assert lib.q8_debug_stream_copy(p, p, 24, None) == SHAPE            # whole 16-byte units only
+    assert lib.q8_debug_stream_copy(p, None, 32, None) == NULL
+    assert lib.q8_debug_stream_copy(p, p, 0, None) == OK
+    assert lib.q8_debug_loop_probe(3, p, p, 4, p, None) == FLAGS           # not one of the built combinations
+    assert lib.q8_debug_loop_probe(7, None, p, 4, p, None) == NULL
+    assert lib.q8_debug_loop_probe(7, p, p, -4, p, None) == SHAPE
     # FP32 attention between the QKV and attention-output FC layers
     lib.q8_attention.argtypes = [vp, i64, i64, C.c_int, C.c_int, vp, C.c_float, vp, vp, vp, vp, vp]
     assert lib.q8_attention(p, -1, 8, 2, 64, None, 0.125, p, None, None, None, None) == SHAPE
