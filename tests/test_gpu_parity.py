@@ -796,3 +796,27 @@ def test_embedding_sum3_empty_table_reads_nothing(q8):
         assert rc == 0
         torch.cuda.synchronize()
         assert host(flag)[0] == 1 and not host(out).any()
+
+
+def test_measurement_kernels(q8):
+    """The benchmark's measurement kernels (not part of the method): the streaming copy copies, the fill fills, and the
+    MFMA-rate loop and every built combination of the main-loop stage probe run to completion inside their windows."""
+    g = synth.rng(311)
+    src = dev(g.standard_normal(1 << 20, dtype=np.float32))
+    dst = torch.zeros(1 << 20, device="cuda")
+    q8.debug_stream_copy(src, dst)
+    assert torch.equal(src, dst)
+    q8.debug_stream_copy(None, dst)
+    assert bool((dst == 1.0).all())
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ops = dev(synth.random_int8(g, (65536,)))
+    assert q8.debug_mfma_rate(ops, 3, 4, sink) == 2.0 * 32768 * 8 * 3 * 8 * 4
+    opw = torch.zeros(4 << 20, dtype=torch.int8, device="cuda")
+    stw = torch.full((8 << 20,), -3.0, device="cuda")
+    guard = torch.full((1024,), -3.0, device="cuda")          # allocated right behind: must stay untouched
+    for what in (0, 7, 15, 64, 71, 79):
+        q8.debug_loop_probe(what, opw, stw, 5, sink)
+    torch.cuda.synchronize()
+    assert int(sink.item()) == 0 and bool((guard == -3.0).all())
+    with pytest.raises(q8.Q8Error):
+        q8.debug_loop_probe(3, opw, stw, 5, sink)
