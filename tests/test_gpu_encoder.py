@@ -169,6 +169,73 @@ def test_bert_large_encoder_layer_stagewise(q8):
     assert host(slots_next).max() == np.abs(host(x_next)).max()
 
 
+def static_layer_stagewise(q8, d, B, S):
+    """The stored-scale layer (Eq. 4) in the chain bench.py times as its stored-scale encoder layer: no quantize pass
+    anywhere -- the attention kernel and both LayerNorms write the int8 codes the next FC reads, FFN1 writes int8
+    through its GELU + requantize epilogue.  Every stage against the oracle on the GPU's own input of that stage; the
+    stored scales are 127 / (0.9 max|.|) of a dynamic pass over the same data, so the clamp is exercised too."""
+    H, F = d["hidden"], d["ffn"]
+    M, heads = B * S, d["heads"]
+    L = Layer(q8, d)
+    w = Work(q8, M, H, F)
+    x_in, slots_x = torch.empty((M, H), device="cuda"), torch.zeros(q8.AMAX_SLOTS, device="cuda")
+    q8.q8_layernorm_absmax(dev(d["x"]), L.gamma[1], L.beta[1], x_in, amax_slots=slots_x)
+    x_next, slots_next = torch.empty((M, H), device="cuda"), torch.zeros(q8.AMAX_SLOTS, device="cuda")
+    gpu_layer(q8, L, w, x_in, slots_x, x_next, slots_next, B, S)            # calibration pass (dynamic scales)
+    torch.cuda.synchronize()
+    sh = (np.float32(127.0) / (np.float32(0.9) * host(w.sc)[0::2])).astype(np.float32)   # x, ctx, h1, gelu(ffn1)
+    s = dev(sh)
+    i8 = lambda *shape: torch.full(shape, 99, dtype=torch.int8, device="cuda")
+    xq_x, xq_c, xq_c2, xq_h, gq, xq_n = i8(M, H), i8(M, H), i8(M, H), i8(M, H), i8(M, F), i8(M, H)
+    g32 = torch.empty((M, F), device="cuda")
+    q8.q8_quantize(x_in, s[0:1], xq_x)
+    q8.q8_linear(xq_x, L.w_qkv, L.b_qkv, s[0:1], L.s_qkv, w.qkv, n_groups=3)
+    q8.q8_attention(w.qkv, B, S, heads, H // heads, ctx=w.ctx, q_scale=s[1:2], q_out=xq_c)
+    q8.q8_attention(w.qkv, B, S, heads, H // heads, q_scale=s[1:2], q_out=xq_c2)          # codes only, as the bench runs it
+    q8.q8_linear(xq_c2, L.w_o, L.b_o, s[1:2], L.s_o, w.attn)
+    q8.q8_layernorm_absmax(x_in, L.gamma[0], L.beta[0], w.h1, residual=w.attn, q_scale=s[2:3], q_out=xq_h)
+    q8.q8_linear(xq_h, L.w_1, L.b_1, s[2:3], L.s_1, gq, next_scale=s[3:4], flags=q8.EPI_GELU | q8.EPI_REQUANT)
+    q8.q8_linear(xq_h, L.w_1, L.b_1, s[2:3], L.s_1, g32, flags=q8.EPI_GELU)                # the fp32 values those codes stand for
+    q8.q8_linear(gq, L.w_2, L.b_2, s[3:4], L.s_2, w.out)
+    q8.q8_layernorm_absmax(w.h1, L.gamma[1], L.beta[1], x_next, residual=w.out, q_scale=s[0:1], q_out=xq_n)
+    torch.cuda.synchronize()
+    x, qkv, ctx, attn, h1, out, xn = (host(t) for t in (x_in, w.qkv, w.ctx, w.attn, w.h1, w.out, x_next))
+    np.testing.assert_array_equal(host(xq_x), O.quantize(x, sh[0]))
+    rel_close(qkv, O.linear(x, L.w_qkv_h, L.s_qkv_h, L.b_qkv_h, sx=sh[0], threads=THREADS)["y"], 1e-6, what="fused QKV")
+    a = O.attention(qkv, B, S, heads, H // heads, threads=THREADS)
+    assert np.abs(ctx.astype(np.float64) - a).max() <= 2e-6 * np.abs(qkv[:, 2 * H:]).max(), "attention"
+    np.testing.assert_array_equal(host(xq_c), O.quantize(ctx, sh[1]))
+    np.testing.assert_array_equal(host(xq_c2), host(xq_c))
+    assert np.abs(host(xq_c)).max() == 127                                   # the stored scale saturates the tail
+    rel_close(attn, O.linear(ctx, L.w_o_h, L.s_o_h, L.b_o_h, sx=sh[1], threads=THREADS)["y"], 1e-6, what="attention output")
+    rel_close(h1, O.layernorm(x, L.gamma_h[0], L.beta_h[0], residual=attn), 1e-6, 2e-7, what="LayerNorm 1")
+    np.testing.assert_array_equal(host(xq_h), O.quantize(h1, sh[2]))
+    r1 = O.linear(h1, L.w_1_h, L.s_1_h, L.b_1_h, sx=sh[2], act_gelu=True, threads=THREADS)
+    gh = host(g32)
+    rel_close(gh, r1["y"], 1e-5, 1e-6, what="FFN1 + GELU")
+    gqh = host(gq)
+    np.testing.assert_array_equal(gqh, O.quantize(gh, sh[3]))               # codes of the GPU's own fp32 values
+    dq = gqh.astype(np.int32) - O.quantize(r1["y"], sh[3]).astype(np.int32)  # against the oracle's: equal up to ties
+    assert np.abs(dq).max() <= 1
+    p = r1["y"].astype(np.float64) * float(sh[3])
+    slack = float(sh[3]) * (1e-6 + 1e-5 * np.abs(r1["y"].astype(np.float64))) + 1e-6 * np.maximum(1.0, np.abs(p))
+    assert np.all(np.abs(np.abs(p - np.trunc(p)) - 0.5)[dq != 0] <= slack[dq != 0])
+    bq2 = O.quantize_bias(L.b_2_h, H, sh[3], np.array([L.s_2_h], np.float32))
+    acc2 = O.gemm_i8(gqh, L.w_2_h, bq2, threads=THREADS)
+    rel_close(out, O.dequant(acc2, sh[3], np.array([L.s_2_h], np.float32)), 1e-6, what="FFN2")
+    rel_close(xn, O.layernorm(h1, L.gamma_h[1], L.beta_h[1], residual=out), 1e-6, 2e-7, what="LayerNorm 2")
+    np.testing.assert_array_equal(host(xq_n), O.quantize(xn, sh[0]))
+
+
+def test_bert_base_encoder_layer_stored_scales_stagewise(q8):
+    static_layer_stagewise(q8, synth.bert_base_layer(seed=2, batch=32, seq=128), 32, 128)
+
+
+def test_bert_large_encoder_layer_stored_scales_stagewise(q8):
+    """The benchmark's stored-scale encoder layer at its own shape: 12288 tokens, hidden 1024, FFN 4096."""
+    static_layer_stagewise(q8, synth.bert_large_layer(seed=3, batch=32, seq=384), 32, 384)
+
+
 def test_bert_base_12_layer_forward(q8):
     """The full BERT-Base forward at batch 64 x seq 128: int8 embedding tables (30522 / 512 / 2 x 768) + LayerNorm,
     then 12 encoder layers, each with its own weights.  Layers 0, 5 and 11 are checked stage by stage against the
