@@ -289,6 +289,21 @@ class Layer:
         q8.q8_linear(self.gq, self.w_2, self.b_2, s[3:4], self.s_2, self.out)
         q8.q8_layernorm_absmax(self.h1f, self.ln_g, self.ln_b, self.x_next, residual=self.out, q_scale=s[0:1], q_out=self.xq_n)
 
+    def step_layer_static_residual_in_fc(self):
+        """step_layer_static with the two residual additions moved from the LayerNorm kernels into the epilogues of the
+        attention-output FC and FFN2 (q8_linear_residual): same traffic, the FC reads the second operand instead."""
+        q8 = self.q8
+        H = self.H
+        s = self.s_static
+        q8.q8_linear(self.xq_x, self.w_qkv, self.b_qkv, s[0:1], self.s_qkv, self.qkv, n_groups=3)
+        q8.q8_attention(self.qkv, self.batch, self.seq, self.heads, H // self.heads, q_scale=s[1:2], q_out=self.xq_c)
+        q8.q8_linear_residual(self.xq_c, self.w_o, self.b_o, s[1:2], self.s_o, self.x_in, self.attn_out)
+        q8.q8_layernorm_absmax(self.attn_out, self.ln_g, self.ln_b, self.h1f, q_scale=s[2:3], q_out=self.xq_h)
+        q8.q8_linear(self.xq_h, self.w_1, self.b_1, s[2:3], self.s_1, self.gq, next_scale=s[3:4],
+                     flags=q8.EPI_GELU | q8.EPI_REQUANT)
+        q8.q8_linear_residual(self.gq, self.w_2, self.b_2, s[3:4], self.s_2, self.h1f, self.out)
+        q8.q8_layernorm_absmax(self.out, self.ln_g, self.ln_b, self.x_next, q_scale=s[0:1], q_out=self.xq_n)
+
     def glue_once(self):
         """Untimed fp32 glue (attention, residual, LayerNorm) so every FC sees realistic inputs."""
         torch = self.torch
@@ -552,6 +567,8 @@ def main():
     out["encoder_layer_static_mode"] = {"ms_per_step": round(dtls * 1e3, 4), "tokens_per_s": round(M / dtls, 1), "steps": n_static,
                                         "note": "stored scales; seven kernels: the attention kernel and both LayerNorms write the "
                                                 "int8 codes the next FC reads, FFN1 writes int8 through its epilogue"}
+    dtlr = timed(torch, layer.step_layer_static_residual_in_fc, n_static, n_warm)
+    out["encoder_layer_static_mode"]["residual_added_in_fc_epilogue_ms_per_step"] = round(dtlr * 1e3, 4)
 
     # ---- the two FFN GEMMs on their own, launched back to back: once on one set of buffers (operands and output stay in
     # the caches) and once rotating through sets that together exceed the 256 MB Infinity Cache

@@ -129,6 +129,22 @@ q8_status q8_linear(const int8_t* xq, const int8_t* wq, const float* bias,
                     uint32_t epilogue_flags, void* stream);
 
 /*
+ * q8_linear with the encoder's residual addition fused into the epilogue: the two FC layers that are followed
+ * by "add the block's input, then Layer Normalization" (attention output and the second feed-forward layer;
+ * both the addition and the normalization stay in FP32, Section 3) write the sum, so that the normalization
+ * reads one tensor instead of two.
+ *     y[m,n] = act(acc[m,n] / (sx * sw[g(n)])) + residual[m,n]        one fp32 addition, round to nearest
+ *   residual fp32[M,N], same layout as y; y may be the residual tensor itself (updated in place).
+ *   flags: Q8_EPI_GELU and Q8_EPI_ABSMAX (of the sum) are accepted, Q8_EPI_REQUANT is not (Q8_ERR_FLAGS).
+ *   Everything else as q8_linear.  Same result as q8_linear followed by an elementwise fp32 addition.
+ */
+q8_status q8_linear_residual(const int8_t* xq, const int8_t* wq, const float* bias,
+                             const float* sx, const float* sw, int n_groups,
+                             int64_t M, int64_t N, int64_t K,
+                             const float* residual, float* y, int32_t* acc_out, float* out_amax,
+                             uint32_t epilogue_flags, void* stream);
+
+/*
  * The dynamic quantizer of Section 4.1 on its own: a = max|x| over the whole tensor, S = 127 / a (Eq. 3; 1.0 when
  * a is 0), q = Quantize(x | S, 127) (Eq. 1) -- two launches (per-workgroup partial maxima, then a quantize pass
  * that folds them), one for tensors of at most 16384 elements.  Same results as q8_absmax followed by q8_quantize.

@@ -58,6 +58,31 @@ q8_status check_linear(const int8_t* xq, const int8_t* wq, const float* bias, co
     return Q8_OK;
 }
 
+// Checks, fills the epilogue and picks the MFMA kernel or the generic one.
+q8_status linear_launch(const int8_t* xq, const int8_t* wq, const float* bias, const float* sx, const float* sw,
+                        int n_groups, int64_t M, int64_t N, int64_t K, void* y, int32_t* acc_out, float* out_amax,
+                        const float* next_scale, const float* residual, uint32_t flags, void* stream)
+{
+    q8_status s = check_linear(xq, wq, bias, sx, sw, n_groups, M, N, K, y, acc_out, out_amax, next_scale, flags);
+    if (s != Q8_OK || M == 0 || N == 0) return s;
+    q8::Epilogue ep;
+    ep.residual = residual;
+    ep.bias = bias;
+    ep.sx = sx;
+    ep.sw = sw;
+    ep.n_groups = n_groups;
+    ep.cols_per_group = (int)(N / n_groups);
+    ep.y = y;
+    ep.acc_out = acc_out;
+    ep.out_amax = out_amax;
+    ep.next_scale = next_scale;
+    ep.flags = flags;
+    int rc = q8::gemm_mfma_eligible(xq, wq, M, N, K)
+                 ? q8::launch_gemm_mfma(xq, wq, M, N, K, ep, as_stream(stream))
+                 : q8::launch_gemm_generic(xq, wq, M, N, K, ep, as_stream(stream));
+    return rc ? Q8_ERR_LAUNCH : Q8_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -104,23 +129,19 @@ q8_status q8_linear(const int8_t* xq, const int8_t* wq, const float* bias, const
                     int n_groups, int64_t M, int64_t N, int64_t K, void* y, int32_t* acc_out, float* out_amax,
                     const float* next_scale, uint32_t flags, void* stream)
 {
-    q8_status s = check_linear(xq, wq, bias, sx, sw, n_groups, M, N, K, y, acc_out, out_amax, next_scale, flags);
-    if (s != Q8_OK || M == 0 || N == 0) return s;
-    q8::Epilogue ep;
-    ep.bias = bias;
-    ep.sx = sx;
-    ep.sw = sw;
-    ep.n_groups = n_groups;
-    ep.cols_per_group = (int)(N / n_groups);
-    ep.y = y;
-    ep.acc_out = acc_out;
-    ep.out_amax = out_amax;
-    ep.next_scale = next_scale;
-    ep.flags = flags;
-    int rc = q8::gemm_mfma_eligible(xq, wq, M, N, K)
-                 ? q8::launch_gemm_mfma(xq, wq, M, N, K, ep, as_stream(stream))
-                 : q8::launch_gemm_generic(xq, wq, M, N, K, ep, as_stream(stream));
-    return rc ? Q8_ERR_LAUNCH : Q8_OK;
+    return linear_launch(xq, wq, bias, sx, sw, n_groups, M, N, K, y, acc_out, out_amax, next_scale, nullptr, flags,
+                         stream);
+}
+
+q8_status q8_linear_residual(const int8_t* xq, const int8_t* wq, const float* bias, const float* sx, const float* sw,
+                             int n_groups, int64_t M, int64_t N, int64_t K, const float* residual, float* y,
+                             int32_t* acc_out, float* out_amax, uint32_t flags, void* stream)
+{
+    if (flags & Q8_EPI_REQUANT) return Q8_ERR_FLAGS;  // the sum is what the FP32 LayerNorm behind it reads
+    if (M > 0 && N > 0 && !residual) return Q8_ERR_NULL;
+    if (misaligned(residual, 4)) return Q8_ERR_ALIGN;
+    return linear_launch(xq, wq, bias, sx, sw, n_groups, M, N, K, y, acc_out, out_amax, nullptr, residual, flags,
+                         stream);
 }
 
 q8_status q8_quantize_dynamic(const float* x, int64_t n, int8_t* q, float* scal_work, float* zero_slot, void* stream)

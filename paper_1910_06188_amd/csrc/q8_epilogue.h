@@ -23,13 +23,14 @@ __device__ __forceinline__ ColConst col_const(const Epilogue& ep, int n, float s
     return c;
 }
 
-// One output element: dequantize, optional GELU, optional requantize; returns the
-// bit pattern of |y| for the optional abs-max.
+// One output element: dequantize, optional GELU, optional residual addition (one fp32 add),
+// optional requantize; returns the bit pattern of |y| for the optional abs-max.
 __device__ __forceinline__ unsigned epilogue_store(const Epilogue& ep, int64_t idx, int acc, float r, float next_scale)
 {
     if (ep.acc_out) ep.acc_out[idx] = acc;
     float y = (float)acc * r;
     if (ep.flags & 1u) y = gelu_erf(y);
+    if (ep.residual) y = __fadd_rn(y, ep.residual[idx]);
     if (ep.flags & 4u)
         reinterpret_cast<int8_t*>(ep.y)[idx] = (int8_t)quantize_code(y, next_scale);
     else

@@ -121,8 +121,8 @@ constexpr int mfma_waves_per_simd(int BM, int BN, int SB, int NW)
 // vmcnt bookkeeping is the same in every trip and no memory is touched.
 //
 // kEpi fixes the epilogue at compile time: 0..5 = that exact combination of Q8_EPI_GELU (1),
-// Q8_EPI_ABSMAX (2) and Q8_EPI_REQUANT (4) with no accumulator dump; -1 = decide at run time
-// (any flags, optional dump).  With one wave per SIMD a per-element run-time branch costs
+// Q8_EPI_ABSMAX (2) and Q8_EPI_REQUANT (4) with no accumulator dump; 8 = no flags, residual
+// added; -1 = decide at run time (any flags, optional dump, optional residual).  With one wave per SIMD a per-element run-time branch costs
 // more than the arithmetic it guards, so the combinations that matter get their own kernel.
 template <int BM, int BN, int WGM, int WGN, int SB, int kEpi>
 __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM* WGN)) void gemm_mfma_kernel(const int8_t* __restrict__ X,
@@ -136,6 +136,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM*
     const bool do_amax = kGen ? (ep.flags & 2u) != 0 : (kEpi & 2) != 0;
     const bool do_req = kGen ? (ep.flags & 4u) != 0 : (kEpi & 4) != 0;
     const bool do_dump = kGen && ep.acc_out != nullptr;
+    const bool do_res = kGen ? ep.residual != nullptr : kEpi == 8;
     constexpr int NW = WGM * WGN;
     constexpr int TM = BM / WGM, TN = BN / WGN;  // wave tile
     constexpr int FM = TM / 32, FN = TN / 32;    // 32x32 MFMA blocks per wave tile
@@ -256,6 +257,38 @@ __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM*
         bias_col[j] = ep.bias ? ep.bias[n] : 0.0f;
     }
 
+    // The descriptors of the epilogue start at the tile's first row, so byte offsets stay below BM * N * 4
+    // whatever the size of y (N * BM * 4 < 2^31 is all that is asked of the shape).
+    const bool interior = (m0 + BM <= M) && (n0 + BN <= N) && ((int64_t)N * BM * 4 < ((int64_t)1 << 31));
+    const int64_t tile_row0 = (int64_t)m0 * N;
+    const int row0 = wm * TM + 4 * hi;  // first row this lane stores, counted from the tile's first row
+
+    // Residual of an interior tile: per 32x32 block 16 loads per lane, each the 2 x 128 contiguous bytes
+    // its store will cover, kept kResAhead blocks ahead of the block being dequantized and stored.  The
+    // first blocks are fetched here, ahead of the main loop, so that no store of the epilogue waits for
+    // a fetch from memory (fetched there, 16 KB in flight per workgroup and the memory latency bound the
+    // whole tile).  They are older than every operand load, so the loop's own counted waits cover them.
+    // y may be the residual tensor itself: every element is read and written by the same lane, the read first.
+    // (The run-time-flag kernel has no registers to spare: it stays one block ahead and starts after the loop.)
+    constexpr int kResAhead = kGen ? 1 : 2, kResSlots = kResAhead + 1;
+    const bool fetch_res = do_res && interior;
+    const __amdgpu_buffer_rsrc_t rres = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(fetch_res ? ep.residual + tile_row0 : ep.residual), 0, fetch_res ? BM * N * 4 : 0, 0x00020000);
+    float res[kResSlots][16];
+    auto fetch_residual = [&](auto bc) {
+        constexpr int b = decltype(bc)::value, j = b / FM, i = b % FM;
+        const int elem0 = row0 * N + n0 + wn * TN + j * 32 + l32;
+        static_for<0, 16>([&](auto ec) {
+            constexpr int e = decltype(ec)::value;
+            constexpr int dm = i * 32 + 8 * (e >> 2) + (e & 3);
+            res[b % kResSlots][e] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rres, elem0 * 4, dm * N * 4, 0));
+        });
+    };
+    auto fetch_first_residuals = [&]() {
+        if (fetch_res) static_for<0, (kResAhead < FM * FN ? kResAhead : FM * FN)>([&](auto bc) { fetch_residual(bc); });
+    };
+    if constexpr (!kGen) fetch_first_residuals();
+
     // Prologue: stages 0 and 1 of both operands; wait for stage 0.
     load_all_a(src_a(0, 0));
     load_all_b(src_b(0, 0));
@@ -360,17 +393,12 @@ __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM*
     // per-lane column offset in a VGPR and the row offset in an SGPR: about six instructions
     // per element.  With one wave per SIMD the epilogue is bound by instruction issue, and
     // the bounds-checked path below costs twice as many.
-    // The descriptors start at the tile's first row, so byte offsets stay below BM * N * 4 whatever
-    // the size of y (N * BM * 4 < 2^31 is all that is asked of the shape).
-    const bool interior = (m0 + BM <= M) && (n0 + BN <= N) && ((int64_t)N * BM * 4 < ((int64_t)1 << 31));
     if (interior) {
         const int esize = do_req ? 1 : 4;
-        const int64_t tile_row0 = (int64_t)m0 * N;
         const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(
             reinterpret_cast<char*>(ep.y) + tile_row0 * esize, 0, BM * N * esize, 0x00020000);
         const __amdgpu_buffer_rsrc_t racc = __builtin_amdgcn_make_buffer_rsrc(
             do_dump ? ep.acc_out + tile_row0 : ep.acc_out, 0, do_dump ? BM * N * 4 : 0, 0x00020000);
-        const int row0 = wm * TM + 4 * hi;  // first row this lane stores, counted from the tile's first row
         // An fp32 y larger than a quarter of the 256 MB Infinity Cache is stored non-temporally:
         // it could not stay cached until its consumer runs anyway, and kept out it neither evicts
         // the next kernels' inputs nor leaves dirty lines to drain under them (whole BERT-Large
@@ -378,6 +406,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM*
         // it).  Smaller outputs are left for the cache to hand to their consumer.
         const bool stream_out = (int64_t)M * N * 4 > ((int64_t)64 << 20);
         float famax = 0.0f;
+        if constexpr (kGen) fetch_first_residuals();
         auto store_tile = [&](auto ntc) {
         constexpr int kAux = decltype(ntc)::value ? 2 : 0;  // aux bit 1 = nt
         static_for<0, FN>([&](auto jc) {
@@ -387,6 +416,10 @@ __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM*
             const int elem0 = row0 * N + n;
             static_for<0, FM>([&](auto ic) {
                 constexpr int i = decltype(ic)::value;
+                constexpr int b = j * FM + i;
+                if constexpr (b + kResAhead < FM * FN) {
+                    if (do_res) fetch_residual(std::integral_constant<int, b + kResAhead>{});
+                }
                 static_for<0, 16>([&](auto ec) {
                     constexpr int e = decltype(ec)::value;
                     constexpr int dm = i * 32 + 8 * (e >> 2) + (e & 3);
@@ -395,6 +428,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, mfma_waves_per_simd(BM, BN, SB, WGM*
                     float yv = (float)a * cc.r;
                     if (do_dump) __builtin_amdgcn_raw_buffer_store_b32((unsigned)a, racc, elem0 * 4, row_elems * 4, 0);
                     if (do_gelu) yv = gelu_erf(yv);
+                    if (do_res) yv = __fadd_rn(yv, res[b % kResSlots][e]);
                     if (do_amax) famax = __builtin_fmaxf(famax, __builtin_fabsf(yv));  // one VALU op: |.| is a source modifier
                     if (do_req)
                         __builtin_amdgcn_raw_buffer_store_b8((unsigned char)quantize_code(yv, next_scale), ry, elem0,
@@ -475,7 +509,7 @@ int launch_tile(const int8_t* xq, const int8_t* wq, int M, int N, int K, int gro
 #define Q8_LAUNCH_EPI(E)                                                                                         \
     hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WGM, WGN, SB, E>), grid, block, 0, st, xq, wq, M, N, K, tiles_n, \
                        group_m, ep)
-    const int epi = (ep.acc_out != nullptr || ep.flags > 5u) ? -1 : (int)ep.flags;
+    const int epi = (ep.acc_out != nullptr || ep.flags > 5u || (ep.residual && ep.flags)) ? -1 : ep.residual ? 8 : (int)ep.flags;
     switch (epi) {
         case 0: Q8_LAUNCH_EPI(0); break;
         case 1: Q8_LAUNCH_EPI(1); break;
@@ -483,6 +517,7 @@ int launch_tile(const int8_t* xq, const int8_t* wq, int M, int N, int K, int gro
         case 3: Q8_LAUNCH_EPI(3); break;
         case 4: Q8_LAUNCH_EPI(4); break;
         case 5: Q8_LAUNCH_EPI(5); break;
+        case 8: Q8_LAUNCH_EPI(8); break;
         default: Q8_LAUNCH_EPI(-1); break;
     }
 #undef Q8_LAUNCH_EPI

@@ -8,7 +8,7 @@
 namespace q8 {
 
 // Everything the GEMM epilogue needs (Section 3: Int32 bias, dequantize; optional
-// fp32 GELU, abs-max of the outputs, requantize with a stored scale).
+// fp32 GELU, the encoder's residual addition, abs-max of the outputs, requantize with a stored scale).
 struct Epilogue {
     const float* bias;        // fp32[N] or null
     const float* sx;          // fp32[1]
@@ -19,6 +19,7 @@ struct Epilogue {
     int32_t* acc_out;         // int32[M,N] or null
     float* out_amax;          // fp32[1] or null
     const float* next_scale;  // fp32[1] or null
+    const float* residual;    // fp32[M,N] added to the fp32 output (may be y itself), or null
     unsigned flags;
 };
 

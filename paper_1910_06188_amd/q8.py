@@ -36,6 +36,8 @@ _lib.q8_scale_from_amax.argtypes = [_vp, _vp, _vp]
 _lib.q8_quantize.argtypes = [_vp, _i64, _vp, _vp, _vp]
 _lib.q8_quantize_amax.argtypes = [_vp, _i64, _vp, _i32, _vp, _vp, _vp, _vp]
 _lib.q8_linear.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _u32, _vp]
+_lib.q8_linear_residual.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _u32, _vp]
+_lib.q8_linear_residual.restype = C.c_int
 _lib.q8_linear_f32.argtypes = [_vp, _vp, _vp, _vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _u32, _vp]
 _lib.q8_embedding.argtypes = [_vp, _vp, _i64, _i64, _vp, _i64, _vp, _i32, _vp, _vp]
 _lib.q8_embedding_sum3.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _vp]
@@ -172,6 +174,19 @@ def q8_linear(xq, wq, bias, sx, sw, y, n_groups=1, acc_out=None, out_amax=None, 
         raise ValueError("q8_linear: scale/bias size mismatch")
     _ck(_lib.q8_linear(_ptr(xq), _ptr(wq), _ptr(bias), _ptr(sx), _ptr(sw), n_groups, M, N, K, _ptr(y),
                        _ptr(acc_out), _ptr(out_amax), _ptr(next_scale), flags, _stream(stream)), "q8_linear")
+
+
+def q8_linear_residual(xq, wq, bias, sx, sw, residual, y, n_groups=1, acc_out=None, out_amax=None, flags=0,
+                       stream=None) -> None:
+    """y = dequant(xq wq^T + quantized bias) + residual: the FC layer with the encoder's residual addition fused."""
+    M, K = xq.shape
+    N, K2 = wq.shape
+    if K != K2 or y.numel() != M * N or residual.numel() != M * N or (acc_out is not None and acc_out.numel() != M * N):
+        raise ValueError("q8_linear_residual: shape mismatch")
+    if sw.numel() != n_groups or (bias is not None and bias.numel() != N):
+        raise ValueError("q8_linear_residual: scale/bias size mismatch")
+    _ck(_lib.q8_linear_residual(_ptr(xq), _ptr(wq), _ptr(bias), _ptr(sx), _ptr(sw), n_groups, M, N, K, _ptr(residual),
+                                _ptr(y), _ptr(acc_out), _ptr(out_amax), flags, _stream(stream)), "q8_linear_residual")
 
 
 def q8_linear_f32(x, wq, bias, sw, xq_work, scal_work, y, n_groups=1, acc_out=None, out_amax=None, next_scale=None,

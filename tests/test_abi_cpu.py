@@ -119,6 +119,13 @@ def test_host_side_argument_checks(lib):
     assert lib.q8_linear_f32_static(p, p, None, p, 1, (64 << 20) // 1024 + 1, 8, 1024, p, None, None, None, 0, None) == TOO_LARGE
     assert lib.q8_linear_f32_static(p, p, None, p, 1, -1, 8, 1024, p, None, None, None, 0, None) == SHAPE
     assert lib.q8_linear_f32_static(p, p, None, p, 1, 4, 8, 128, p, p + 2, None, None, 0, None) == ALIGN
+    # the FC layer with the residual addition fused: fp32 output only, the residual is required
+    lib.q8_linear_residual.argtypes = [vp, vp, vp, vp, vp, C.c_int, i64, i64, i64, vp, vp, vp, vp, C.c_uint32, vp]
+    assert lib.q8_linear_residual(p, p, None, p, p, 1, 4, 4, 128, p, p, None, None, 4, None) == FLAGS
+    assert lib.q8_linear_residual(p, p, None, p, p, 1, 4, 4, 128, None, p, None, None, 0, None) == NULL
+    assert lib.q8_linear_residual(p, p, None, p, p, 1, 4, 4, 128, p + 2, p, None, None, 0, None) == ALIGN
+    assert lib.q8_linear_residual(p, p, None, p, p, 1, 4, 4, 128, p, p, None, None, 2, None) == FLAGS   # abs-max without its slot
+    assert lib.q8_linear_residual(None, None, None, None, None, 1, 0, 4, 128, None, None, None, None, 0, None) == 0
     # the dynamic quantizer on its own, and the measurement kernels' argument checks
     lib.q8_quantize_dynamic.argtypes = [vp, i64, vp, vp, vp, vp]
     assert lib.q8_quantize_dynamic(p, -1, p, p, None, None) == SHAPE

@@ -225,6 +225,21 @@ def static_layer_stagewise(q8, d, B, S):
     rel_close(out, O.dequant(acc2, sh[3], np.array([L.s_2_h], np.float32)), 1e-6, what="FFN2")
     rel_close(xn, O.layernorm(h1, L.gamma_h[1], L.beta_h[1], residual=out), 1e-6, 2e-7, what="LayerNorm 2")
     np.testing.assert_array_equal(host(xq_n), O.quantize(xn, sh[0]))
+    # The same two sub-layers with the residual addition moved into the FC epilogue: the FC writes x + FC(ctx)
+    # (one binary32 addition, as in the oracle's LayerNorm), the LayerNorm behind it reads that one tensor.
+    sum1, sum2, h1_f, xn_f = (torch.empty((M, H), device="cuda") for _ in range(4))
+    xq_hf, xq_nf = i8(M, H), i8(M, H)
+    q8.q8_linear_residual(xq_c2, L.w_o, L.b_o, s[1:2], L.s_o, x_in, sum1)
+    q8.q8_layernorm_absmax(sum1, L.gamma[0], L.beta[0], h1_f, q_scale=s[2:3], q_out=xq_hf)
+    q8.q8_linear_residual(gq, L.w_2, L.b_2, s[3:4], L.s_2, w.h1, sum2)
+    q8.q8_layernorm_absmax(sum2, L.gamma[1], L.beta[1], xn_f, q_scale=s[0:1], q_out=xq_nf)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(sum1), attn + x)
+    np.testing.assert_array_equal(host(sum2), out + h1)
+    rel_close(host(h1_f), O.layernorm(x, L.gamma_h[0], L.beta_h[0], residual=attn), 1e-6, 2e-7, what="LayerNorm 1 of the fused sum")
+    np.testing.assert_array_equal(host(xq_hf), O.quantize(host(h1_f), sh[2]))
+    rel_close(host(xn_f), O.layernorm(h1, L.gamma_h[1], L.beta_h[1], residual=out), 1e-6, 2e-7, what="LayerNorm 2 of the fused sum")
+    np.testing.assert_array_equal(host(xq_nf), O.quantize(host(xn_f), sh[0]))
 
 
 def test_bert_base_encoder_layer_stored_scales_stagewise(q8):

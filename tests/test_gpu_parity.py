@@ -484,6 +484,59 @@ def test_linear_specialised_epilogues(q8, M, K, N):
     assert host(am)[0] == np.abs(host(y)).max()
 
 
+@pytest.mark.parametrize("M,K,N,variant", [
+    (768, 256, 512, 0), (768, 256, 512, 1), (768, 256, 512, 2), (768, 256, 512, 3), (768, 256, 512, 4), (768, 256, 512, 5),
+    (768, 256, 512, 6), (700, 384, 600, 0), (700, 384, 600, 2), (700, 384, 600, 3), (700, 384, 600, 5), (700, 384, 600, 6),
+    (257, 128, 129, 0), (1, 128, 1, 0), (1030, 1024, 2100, 0), (33, 100, 70, 0), (5, 1, 3, 0),
+])
+def test_linear_residual_epilogue(q8, M, K, N, variant):
+    """The FC layer with the encoder's residual addition fused (Section 3: the addition stays FP32): one binary32
+    addition on top of the dequantized output.  Interior and edge tiles of every tile shape, the generic kernel, the
+    run-time-flag kernel (abs-max of the sum, accumulator dump, GELU) and the in-place form."""
+    d = synth.fc_layer(4000 + M + N + variant, M, K, N)
+    rng = np.random.default_rng(77 + M + variant)
+    wq_h, sw_h = O.quantize_tensor(d["W"])
+    ref = O.linear(d["x"], wq_h, np.array([sw_h], np.float32), d["b"], threads=8)
+    res_h = (rng.standard_normal((M, N)) * max(float(np.abs(ref["y"]).max()), 1e-3) * 0.5).astype(np.float32)
+    xq, wq, sx, sw, b, res = dev(ref["xq"]), dev(wq_h), scalar(float(ref["sx"])), scalar(float(sw_h)), dev(d["b"]), dev(res_h)
+    y0, y1, y2, y3 = (torch.empty((M, N), device="cuda") for _ in range(4))
+    acc, amax, amax_g = torch.empty((M, N), dtype=torch.int32, device="cuda"), scalar(0.0), scalar(0.0)
+    y_inplace = res.clone()
+    q8.set_gemm_variant(variant)
+    try:
+        q8.q8_linear(xq, wq, b, sx, sw, y0)
+        q8.q8_linear_residual(xq, wq, b, sx, sw, res, y1)                                   # the dedicated kernel
+        q8.q8_linear_residual(xq, wq, b, sx, sw, res, y2, acc_out=acc, out_amax=amax, flags=q8.EPI_ABSMAX)
+        q8.q8_linear_residual(xq, wq, b, sx, sw, res, y3, out_amax=amax_g, flags=q8.EPI_GELU | q8.EPI_ABSMAX)
+        q8.q8_linear_residual(xq, wq, b, sx, sw, y_inplace, y_inplace)
+        yg = torch.empty((M, N), device="cuda")
+        q8.q8_linear(xq, wq, b, sx, sw, yg, flags=q8.EPI_GELU)
+    finally:
+        q8.set_gemm_variant(0)
+    torch.cuda.synchronize()
+    y0h, y1h = host(y0), host(y1)
+    np.testing.assert_array_equal(host(acc), ref["acc"])
+    np.testing.assert_array_equal(y1h, y0h + res_h)                  # exactly the unfused output plus one fp32 addition
+    np.testing.assert_array_equal(host(y2), y1h)
+    np.testing.assert_array_equal(host(y_inplace), y1h)
+    np.testing.assert_array_equal(host(y3), host(yg) + res_h)        # activation first, then the addition
+    assert host(amax)[0] == np.abs(y1h).max() and host(amax_g)[0] == np.abs(host(y3)).max()
+    exact = ref["y"].astype(np.float64) + res_h.astype(np.float64)   # and against the oracle's FC output
+    assert np.all(np.abs(y1h.astype(np.float64) - exact) <= 1e-6 * np.abs(ref["y"]) + 6e-8 * np.abs(exact) + 1e-30)
+
+
+def test_linear_residual_argument_checks(q8):
+    xq, wq = torch.zeros((4, 128), dtype=torch.int8, device="cuda"), torch.zeros((4, 128), dtype=torch.int8, device="cuda")
+    y, s = torch.empty((4, 4), device="cuda"), scalar(1.0)
+    with pytest.raises(q8.Q8Error) as e:
+        q8.q8_linear_residual(xq, wq, None, s, s, y, y, flags=q8.EPI_REQUANT)
+    assert e.value.code == 4
+    import ctypes
+    assert q8._lib.q8_linear_residual(xq.data_ptr(), wq.data_ptr(), None, s.data_ptr(), s.data_ptr(), 1, 4, 4, 128, None,
+                                      y.data_ptr(), None, None, 0, None) == 1                       # residual missing
+    assert q8._lib.q8_linear_residual(None, None, None, None, None, 1, 0, 4, 128, None, None, None, None, 0, None) == 0
+
+
 def test_linear_static_activation_scale(q8):
     d = synth.fc_layer(46, 150, 256, 200)
     sx = np.float32(20.0)                                   # stored scale: values beyond 6.35 saturate
