@@ -147,7 +147,9 @@ q8_status q8_linear_residual(const int8_t* xq, const int8_t* wq, const float* bi
 /*
  * The dynamic quantizer of Section 4.1 on its own: a = max|x| over the whole tensor, S = 127 / a (Eq. 3; 1.0 when
  * a is 0), q = Quantize(x | S, 127) (Eq. 1) -- two launches (per-workgroup partial maxima, then a quantize pass
- * that folds them), one for tensors of at most 16384 elements.  Same results as q8_absmax followed by q8_quantize.
+ * that folds them); one launch for tensors of at most 16384 elements, and one launch that reads x only once for
+ * tensors the chip can hold in registers between the two steps (up to 12.5 M elements on 256 compute units; see
+ * q8_debug_set_quantize_one_pass).  Same results as q8_absmax followed by q8_quantize in every case.
  *   x fp32[n]; q int8[n]; n >= 0 (n = 0: a = 0, S = 1).
  *   scal_work fp32[Q8_SCAL_WORK], caller-provided scratch: on return scal_work[0] = a, scal_work[1] = S (a device
  *   scalar to hand to q8_linear as sx); the rest holds the partial maxima.
@@ -358,6 +360,17 @@ q8_status q8_attention(const float* qkv, int64_t B, int64_t S, int heads, int d,
  * while no other thread is inside q8_linear.  An unknown variant makes q8_linear return Q8_ERR_LAUNCH.
  */
 void q8_debug_set_gemm_variant(int variant);
+
+/*
+ * The dynamic quantizer (q8_quantize_dynamic, q8_linear_f32, q8_linear_f32_static) takes a one-pass kernel for
+ * tensors that fit the register files of the chip: 4-element multiples of n between 4096 and 49152 floats per
+ * compute unit, x 16-byte aligned, stream not under graph capture.  Its workgroups meet at a barrier; one that has
+ * polled `barrier_polls` times (default 64, about 80 us) stops waiting and reads the shares of the absent
+ * workgroups itself, so the result never depends on the wait.  enabled = 0 turns the kernel off (two passes over
+ * x, same results); barrier_polls = 0 makes a workgroup scan for every other one that is not there at its first
+ * look (tests).  Process-global, unsynchronised.
+ */
+void q8_debug_set_quantize_one_pass(int enabled, uint32_t barrier_polls);
 
 /*
  * Measurement kernels for the benchmark: what the chip sustains next to the library's own kernels.

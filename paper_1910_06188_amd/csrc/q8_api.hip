@@ -155,6 +155,9 @@ q8_status q8_quantize_dynamic(const float* x, int64_t n, int8_t* q, float* scal_
         // a tensor one workgroup can hold in registers (an empty one included): abs-max, scale and quantize in a single launch
         return q8::launch_quantize_onepass(x, n, scal_work, scal_work + 1, q, zero_slot, st) ? Q8_ERR_LAUNCH : Q8_OK;
     }
+    // a tensor the chip's registers can hold between the reduction and the rounding: one pass, x read once
+    const int one_pass = q8::launch_quantize_resident(x, n, scal_work, scal_work + 1, q, zero_slot, st);
+    if (one_pass != 2) return one_pass ? Q8_ERR_LAUNCH : Q8_OK;
     // abs-max slots in scal_work[2..], folded by the quantize kernel: no atomics, no extra launch
     int slots = 0;
     if (q8::launch_absmax_partial(x, n, scal_work + 2, &slots, st)) return Q8_ERR_LAUNCH;
@@ -397,5 +400,10 @@ q8_status q8_debug_stream_copy(const void* src, void* dst, int64_t nbytes, void*
 
 /* Tuning hook for the benchmark (not part of the method): pick the MFMA tile variant, 0 = automatic. */
 void q8_debug_set_gemm_variant(int v) { q8::set_gemm_variant(v); }
+
+void q8_debug_set_quantize_one_pass(int enabled, uint32_t barrier_polls)
+{
+    q8::set_quantize_resident(enabled != 0, barrier_polls);
+}
 
 }  // extern "C"

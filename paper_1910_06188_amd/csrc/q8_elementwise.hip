@@ -3,6 +3,9 @@
 // Eq. 4 and the straight-through gradient (Eq. 5).  All are single passes over fp32 data and
 // are bound by HBM bandwidth: abs-max reads 4 B per element, quantize reads 4 B and writes
 // 1 B, fake quantization and the gradient copy read 4 B and write 4 B.
+#include <atomic>
+#include <mutex>
+
 #include "q8_device.h"
 #include "q8_launch.h"
 
@@ -406,6 +409,187 @@ int launch_quantize_onepass(const float* x, int64_t n, float* amax_out, float* s
                             hipStream_t st)
 {
     hipLaunchKernelGGL(quantize_onepass_kernel, dim3(1), dim3(kEwThreads), 0, st, x, (int)n, amax_out, scale_out, q, zero_slot);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+// ---- The dynamic quantizer in one pass over x (Section 4.1: abs-max of the incoming tensor, Eq. 3, then Eq. 1).
+//
+// The abs-max has to be complete before the first code can be formed, which is why the plain path reads x twice
+// (9 bytes of traffic per element).  The register files of the chip (512 KiB per compute unit, 128 MiB in all)
+// are larger than the activation tensors of an encoder layer (50 MB at 12288 tokens x 1024), so this kernel
+// keeps the tensor in registers across the reduction: every workgroup loads its share (up to 48 floats per
+// thread), leaves its maximum in a slot, waits at a grid-wide barrier, folds the slots, and quantizes from
+// registers -- 5 bytes per element, x read once.
+//
+// The barrier needs every workgroup of the launch to be resident at once: the grid is one workgroup of 1024
+// threads per compute unit, so it is whenever the chip is not held by something else; and no wait is unbounded --
+// a workgroup that has polled `spin_limit` times stops waiting and reads the shares of the workgroups that have
+// not published yet itself (same result, slower; what two such launches from different streams that each hold
+// part of the chip fall back to).
+//
+// The barrier has no counter (256 read-modify-writes on one address serialise at the memory side, and the
+// release/acquire fences around them write back and invalidate a whole L2 each: together 10 us): every workgroup
+// publishes (ticket, maximum) as one 64-bit atomic store into its own slot, and one wave per workgroup polls all
+// slots until each carries this launch's ticket.  Tickets come from a host-side counter, so a slot never carries
+// the current ticket before its workgroup has written it; the slots are library-owned (zero when the code object
+// is loaded, written by this kernel only), handed out round robin from a ring.  Should two launches in flight
+// ever share a ring entry they overwrite each other's slots, which can only make a workgroup stop waiting and
+// scan -- never use a maximum that is not its launch's.
+constexpr int kRqThreads = 1024;
+constexpr int kRqVec = 12;  // float4 per thread
+constexpr int kRqMaxGroups = 256;
+constexpr int kRqRing = 64;
+static __device__ unsigned long long g_rq_slots[kRqRing][kRqMaxGroups];
+
+__global__ __launch_bounds__(kRqThreads) void quantize_resident_kernel(const float4* __restrict__ x4, int n4, int chunk4,
+                                                                        unsigned long long* slots, unsigned ticket,
+                                                                        unsigned spin_limit, float* amax_out,
+                                                                        float* scale_out, unsigned* __restrict__ q4,
+                                                                        float* zero_slot)
+{
+    __shared__ unsigned wave_part[kRqThreads / 64];
+    __shared__ unsigned folded;
+    __shared__ unsigned long long missing[kRqMaxGroups / 64];
+    const int G = (int)gridDim.x, w = (int)blockIdx.x, t = (int)threadIdx.x;
+    const int first = w * chunk4, last = min(first + chunk4, n4);
+    float4 v[kRqVec];
+    unsigned m = 0u;
+#pragma unroll
+    for (int k = 0; k < kRqVec; ++k) {
+        const int idx = first + k * kRqThreads + t;
+        v[k] = idx < last ? load_f4_nt(&x4[idx]) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    }
+#pragma unroll
+    for (int k = 0; k < kRqVec; ++k)
+        m = max(m, max(max(abs_bits(v[k].x), abs_bits(v[k].y)), max(abs_bits(v[k].z), abs_bits(v[k].w))));
+    m = wave_max_u32(m);
+    if ((t & 63) == 0) wave_part[t >> 6] = m;
+    __syncthreads();
+    if (t < 64) {
+        const unsigned wm = wave_max_u32(t < kRqThreads / 64 ? wave_part[t] : 0u);
+        if (t == 0)
+            __hip_atomic_store(&slots[w], ((unsigned long long)ticket << 32) | wm, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        unsigned a = 0u;
+        for (unsigned polls = 0;; ++polls) {
+            a = 0u;
+            bool all_here = true;
+#pragma unroll
+            for (int r = 0; r < kRqMaxGroups / 64; ++r) {
+                const int i = r * 64 + t;
+                bool here = true;  // slots past the grid count as arrived
+                if (i < G) {
+                    const unsigned long long sv = __hip_atomic_load(&slots[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    here = (unsigned)(sv >> 32) == ticket;
+                    if (here) a = max(a, (unsigned)sv);
+                }
+                const unsigned long long absent = __ballot(!here);
+                if (t == 0) missing[r] = absent;
+                all_here = all_here && absent == 0ull;
+            }
+            if (all_here || polls >= spin_limit) break;  // bounded: after spin_limit polls the absent ones are scanned below
+            __builtin_amdgcn_s_sleep(8);
+        }
+        a = wave_max_u32(a);
+        if (t == 0) folded = a;
+    }
+    __syncthreads();
+    // Workgroups that had not published their maximum when this one stopped waiting: their shares of x are read
+    // here instead (each element's maximum is the same whoever takes it), so the result never depends on the wait.
+    unsigned extra = 0u;
+    bool scanned = false;
+#pragma unroll 1
+    for (int r = 0; r < kRqMaxGroups / 64; ++r) {
+        unsigned long long absent = missing[r];
+        while (absent) {
+            const int g = r * 64 + __builtin_ctzll(absent);
+            absent &= absent - 1ull;
+            scanned = true;
+            const int gfirst = g * chunk4, glast = min(gfirst + chunk4, n4);
+            for (int i = gfirst + t; i < glast; i += kRqThreads) {
+                const float4 u = x4[i];
+                extra = max(extra, max(max(abs_bits(u.x), abs_bits(u.y)), max(abs_bits(u.z), abs_bits(u.w))));
+            }
+        }
+    }
+    if (scanned) {  // uniform over the workgroup: `missing` is shared
+        extra = wave_max_u32(extra);
+        if ((t & 63) == 0) wave_part[t >> 6] = extra;  // its first contents were read before the barrier above
+        __syncthreads();
+        if (t == 0) {
+            for (int i = 0; i < kRqThreads / 64; ++i) folded = max(folded, wave_part[i]);
+        }
+        __syncthreads();
+    }
+    const float a = __uint_as_float(folded);
+    const float s = scale_from_amax(a);
+    if (w == 0 && t == 0) {
+        amax_out[0] = a;
+        scale_out[0] = s;
+        if (zero_slot) zero_slot[0] = 0.0f;
+    }
+#pragma unroll
+    for (int k = 0; k < kRqVec; ++k) {
+        const int idx = first + k * kRqThreads + t;
+        if (idx < last) q4[idx] = pack4(v[k], s);
+    }
+}
+
+static std::atomic<unsigned> g_rq_next{0};
+static std::atomic<unsigned> g_rq_spin_limit{64u};   // about 80 us of polling
+static std::atomic<bool> g_rq_enabled{true};
+static std::mutex g_rq_lock;
+static unsigned long long* g_rq_slots_ptr[64] = {};
+static int g_rq_groups[64] = {};
+
+void set_quantize_resident(bool enabled, unsigned polls)
+{
+    g_rq_enabled.store(enabled);
+    g_rq_spin_limit.store(polls);
+}
+
+// 0: launched.  1: the runtime refused the launch.  2: not a case for this kernel (the caller takes the two-pass path):
+// shape or alignment, a tensor larger than the registers of the grid, a stream under graph capture (a replay would
+// carry the ticket of the capture), or a device the slot ring cannot be looked up on.
+int launch_quantize_resident(const float* x, int64_t n, float* amax_out, float* scale_out, int8_t* q, float* zero_slot,
+                             hipStream_t st)
+{
+    if (!g_rq_enabled.load()) return 2;
+    if (n % 4 != 0 || (reinterpret_cast<uintptr_t>(x) & 15) || (reinterpret_cast<uintptr_t>(q) & 3)) return 2;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 2;
+    unsigned long long* ring = nullptr;
+    int groups = 0;
+    {
+        std::lock_guard<std::mutex> hold(g_rq_lock);
+        if (!g_rq_slots_ptr[dev]) {
+            void* p = nullptr;
+            int cus = 0;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_rq_slots)) != hipSuccess ||
+                hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) {
+                (void)hipGetLastError();
+                return 2;
+            }
+            g_rq_slots_ptr[dev] = static_cast<unsigned long long*>(p);
+            g_rq_groups[dev] = cus < kRqMaxGroups ? cus : kRqMaxGroups;
+        }
+        ring = g_rq_slots_ptr[dev];
+        groups = g_rq_groups[dev];
+    }
+    const int64_t n4 = n >> 2;
+    if (n4 < (int64_t)groups * kRqThreads || n4 > (int64_t)groups * kRqThreads * kRqVec) return 2;
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cap) != hipSuccess) {
+        (void)hipGetLastError();
+        return 2;
+    }
+    if (cap != hipStreamCaptureStatusNone) return 2;
+    const int chunk4 = (int)((n4 + groups - 1) / groups);
+    unsigned seq = g_rq_next.fetch_add(1u);
+    const unsigned ticket = seq + 1u == 0u ? g_rq_next.fetch_add(1u) + 1u : seq + 1u;   // never 0: the slots start as zeros
+    unsigned long long* slots = ring + (size_t)(seq % kRqRing) * kRqMaxGroups;
+    hipLaunchKernelGGL(quantize_resident_kernel, dim3(groups), dim3(kRqThreads), 0, st, reinterpret_cast<const float4*>(x),
+                       (int)n4, chunk4, slots, ticket, g_rq_spin_limit.load(), amax_out, scale_out,
+                       reinterpret_cast<unsigned*>(q), zero_slot);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 

@@ -33,6 +33,13 @@ int launch_quantize_amax(const float* x, int64_t n, const float* amax, int n_ama
 int quantize_onepass_max();
 int launch_quantize_onepass(const float* x, int64_t n, float* amax_out, float* scale_out, int8_t* q, float* zero_slot,
                             hipStream_t st);
+// Tensors that fit the chip's register files: abs-max, scale and quantize in one pass over x with a grid-wide barrier
+// in between (q8_elementwise.hip).  Returns 2 when the case is not one for this kernel: take the two-pass path then.
+int launch_quantize_resident(const float* x, int64_t n, float* amax_out, float* scale_out, int8_t* q, float* zero_slot,
+                             hipStream_t st);
+// Tuning hook: switch that kernel off, or set how often a workgroup polls the barrier before it stops waiting and scans
+// x itself (0: never wait -- the tests run the give-up path that way).
+void set_quantize_resident(bool enabled, unsigned polls);
 int launch_scale_from_amax(const float* amax, float* scale_out, hipStream_t st);
 int launch_quantize(const float* x, int64_t n, const float* scale, int8_t* q, hipStream_t st);
 

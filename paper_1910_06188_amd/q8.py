@@ -69,6 +69,8 @@ _lib.q8_status_str.restype = C.c_char_p
 _lib.q8_status_str.argtypes = [C.c_int]
 _lib.q8_debug_set_gemm_variant.argtypes = [C.c_int]
 _lib.q8_debug_set_gemm_variant.restype = None
+_lib.q8_debug_set_quantize_one_pass.argtypes = [C.c_int, _u32]
+_lib.q8_debug_set_quantize_one_pass.restype = None
 
 
 class Q8Error(RuntimeError):
@@ -107,6 +109,11 @@ def status_str(code: int) -> str:
 
 def set_gemm_variant(v: int) -> None:
     _lib.q8_debug_set_gemm_variant(int(v))
+
+
+def set_quantize_one_pass(enabled: bool = True, barrier_polls: int = 64) -> None:
+    """Tuning hook of the dynamic quantizer's one-pass kernel (off: two passes; barrier_polls 0: never wait)."""
+    _lib.q8_debug_set_quantize_one_pass(1 if enabled else 0, int(barrier_polls))
 
 
 def q8_absmax(x, amax_out, scale_out=None, stream=None) -> None:

@@ -68,6 +68,33 @@ def test_dynamic_ffn_chain_under_graph_capture(q8):
         assert float(y.abs().max()) > 0
 
 
+def test_dynamic_quantizer_of_a_large_tensor_under_graph_capture(q8):
+    """A tensor in the size range of the one-pass quantizer: under capture the library takes the two-pass kernels (the
+    one-pass kernel's barrier ticket comes from the host and would be the same on every replay), so replays on new
+    data give the eager result -- which runs the one-pass kernel."""
+    n = 3_145_728
+    x = torch.randn(n, device="cuda")
+    q, scal = torch.empty(n, dtype=torch.int8, device="cuda"), torch.zeros(q8.SCAL_WORK, device="cuda")
+    q8.q8_quantize_dynamic(x, q, scal)
+    torch.cuda.synchronize()
+    graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            q8.q8_quantize_dynamic(x, q, scal)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        x.copy_(torch.randn(n, device="cuda") * (0.5 + rep))
+        q.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        q_graph, s_graph = q.clone(), scal[:2].clone()
+        q.zero_()
+        q8.q8_quantize_dynamic(x, q, scal)
+        torch.cuda.synchronize()
+        assert torch.equal(q_graph, q) and torch.equal(s_graph, scal[:2]), rep
+        assert int(q.abs().max()) == 127
+
+
 def test_attention_block_under_graph_capture(q8):
     """LayerNorm (abs-max slots) -> quantize -> fused QKV FC -> FP32 attention (abs-max slots) -> quantize ->
     attention-output FC -> residual + LayerNorm: the first half of an encoder layer, captured and replayed."""

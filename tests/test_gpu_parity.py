@@ -746,6 +746,72 @@ def test_quantize_dynamic_is_absmax_scale_quantize(q8, n):
         np.testing.assert_array_equal(host(q), O.quantize(x, s))
 
 
+@pytest.mark.parametrize("mode", ["one_pass", "never_wait", "two_pass"])
+@pytest.mark.parametrize("n,where", [(1_048_576, 0), (1_048_580, -1), (3_145_728, 1_500_000), (12_582_908, -1),
+                                     (12_582_912, 0), (12_582_912, 6_000_001), (12_582_912, -1)])
+def test_quantize_dynamic_register_resident_sizes(q8, n, where, mode):
+    """Section 4.1 on tensors the one-pass kernel takes (x stays in registers between the abs-max and Eq. 1; its
+    workgroups meet at a barrier): the kernel as it runs, the same with a barrier that never waits (every workgroup
+    reads the shares of those it does not see yet), and the two-pass path, each against the oracle.  The extreme
+    value sits in the first, a middle or the last workgroup's share and is negative."""
+    rng = np.random.default_rng(900 + n % 1000 + (where % 7))
+    x = rng.standard_normal(n).astype(np.float32)
+    x[where] = np.float32(-11.5)
+    xd, q = dev(x), torch.full((n,), 99, dtype=torch.int8, device="cuda")
+    scal, z = torch.full((q8.SCAL_WORK,), 7.0, device="cuda"), scalar(5.0)
+    q8.set_quantize_one_pass(mode != "two_pass", 0 if mode == "never_wait" else 64)
+    try:
+        q8.q8_quantize_dynamic(xd, q, scal, zero_slot=z)
+        torch.cuda.synchronize()
+    finally:
+        q8.set_quantize_one_pass(True, 64)
+    q_ref, s_ref = O.quantize_tensor(x)
+    sh = host(scal)
+    assert sh[0] == np.float32(11.5) and sh[1] == s_ref and host(z)[0] == 0.0
+    np.testing.assert_array_equal(host(q), q_ref)
+
+
+def test_quantize_dynamic_one_pass_all_zero_and_repeated_calls(q8):
+    """An all-zero tensor takes S = 1; and the barrier's slots carry a new ticket on every launch, so a maximum
+    left by an earlier, larger tensor is never picked up."""
+    n = 2_097_152
+    q, scal = torch.full((n,), 99, dtype=torch.int8, device="cuda"), torch.zeros(q8.SCAL_WORK, device="cuda")
+    big = torch.full((n,), 1000.0, device="cuda")
+    for rep in range(70):                                   # more launches than the ring of slot sets is long
+        q8.q8_quantize_dynamic(big, q, scal)
+    q8.q8_quantize_dynamic(torch.zeros(n, device="cuda"), q, scal)
+    torch.cuda.synchronize()
+    assert host(scal)[0] == 0.0 and host(scal)[1] == 1.0 and not host(q).any()
+    x = np.random.default_rng(5).standard_normal(n).astype(np.float32)
+    q8.q8_quantize_dynamic(dev(x), q, scal)
+    torch.cuda.synchronize()
+    q_ref, s_ref = O.quantize_tensor(x)
+    assert host(scal)[1] == s_ref
+    np.testing.assert_array_equal(host(q), q_ref)
+
+
+def test_quantize_dynamic_one_pass_on_two_streams(q8):
+    """Two one-pass launches in flight at once, each needing the whole chip for its barrier to open: whichever way the
+    hardware interleaves them (one after the other, or each holding part of the compute units until the bounded wait
+    runs out and the absent shares are read instead) both results are the oracle's."""
+    n = 12_582_912
+    rng = np.random.default_rng(31)
+    xs = [rng.standard_normal(n).astype(np.float32) * np.float32(1 + i) for i in range(2)]
+    xd = [dev(x) for x in xs]
+    qs = [torch.full((n,), 99, dtype=torch.int8, device="cuda") for _ in range(2)]
+    scals = [torch.zeros(q8.SCAL_WORK, device="cuda") for _ in range(2)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for rep in range(5):
+        for i in range(2):
+            q8.q8_quantize_dynamic(xd[i], qs[i], scals[i], stream=streams[i])
+    torch.cuda.synchronize()
+    for i in range(2):
+        q_ref, s_ref = O.quantize_tensor(xs[i])
+        assert host(scals[i])[1] == s_ref
+        np.testing.assert_array_equal(host(qs[i]), q_ref)
+
+
 def test_linear_is_deterministic(q8):
     d = synth.fc_layer(48, 600, 512, 700)
     a = run_linear(q8, d["x"], d["W"], d["b"])
