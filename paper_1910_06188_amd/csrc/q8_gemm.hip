@@ -98,9 +98,9 @@ int launch_gemm_mfma(const int8_t* xq, const int8_t* wq, int64_t M64, int64_t N6
             const double rounds = (double)full + (rem == 0 ? 0.0 : (c.per_cu == 2 && rem <= 256) ? 0.6 : 1.0);
             const double slots_used = ((double)tiles / (double)slots) / rounds;
             double prior = K >= 2048 ? c.prior_long : (int8_out ? c.prior_short_i8 : c.prior_short_f32);
-            // a short reduction whose fp32 epilogue carries the GELU is bound by that epilogue's vector arithmetic: the
-            // 256x256 tile (least operand traffic per output) wins it inside the layer step by 6 us of 85
-            if (K < 2048 && !int8_out && (ep.flags & 1u) && c.variant == 2) prior = 1.04;
+            // a short reduction whose fp32 epilogue carries the GELU: inside the layer step the paired 192x128 tile
+            // wins it (314 us for the whole dynamic step against 320 with 256x256 and 321 with 128x128)
+            if (K < 2048 && !int8_out && (ep.flags & 1u) && c.variant == 6) prior = 1.05;
             const double score = prior * slots_used * inside;
             if (score > best) {
                 best = score;
