@@ -166,6 +166,11 @@ q8_status q8_quantize_dynamic(const float* x, int64_t n, int8_t* q, float* scal_
  *   Other arguments as q8_linear, with one convenience: with Q8_EPI_ABSMAX this call sets
  *   out_amax[0] to 0 itself before the GEMM accumulates into it (q8_linear leaves that to the
  *   caller), so on return out_amax[0] = max|y| of this call alone.
+ *   Launches: two (quantizer, GEMM) -- the quantizer is one launch whenever x has at most 16384 elements or
+ *   fits the chip's registers (q8_quantize_dynamic) -- and a single one for a handful of tokens (M <= 32,
+ *   M * K <= 16384, K a multiple of 128 up to 1024, 16-byte aligned x and wq, 4-byte aligned xq_work, no
+ *   Q8_EPI_ABSMAX): there the layer is bound by launch latency, so every workgroup quantizes x itself and keeps
+ *   the codes on chip.  Results do not depend on the path taken.
  */
 q8_status q8_linear_f32(const float* x, const int8_t* wq, const float* bias,
                         const float* sw, int n_groups,

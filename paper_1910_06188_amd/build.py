@@ -11,7 +11,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libq8.so")
 SOURCES = ["q8_api.hip", "q8_elementwise.hip", "q8_gemm.hip", "q8_embedding.hip",
            "q8_gemm_tile_256x256_w4.hip", "q8_gemm_tile_256x256_w8.hip", "q8_gemm_tile_128x128_w4.hip",
-           "q8_gemm_tile_192x256_w4.hip", "q8_gemm_tile_192x256_w8.hip", "q8_gemm_tile_192x128_w4.hip", "q8_layernorm.hip", "q8_attention.hip", "q8_ceiling.hip"]
+           "q8_gemm_tile_192x256_w4.hip", "q8_gemm_tile_192x256_w8.hip", "q8_gemm_tile_192x128_w4.hip", "q8_layernorm.hip", "q8_attention.hip", "q8_ceiling.hip", "q8_fc_small.hip"]
 OBJ_DIR = os.path.join(HERE, "_build")
 
 # -ffp-contract=off: the product x*S of Eq. 1 must be rounded on its own before the

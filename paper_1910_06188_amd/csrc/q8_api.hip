@@ -58,13 +58,10 @@ q8_status check_linear(const int8_t* xq, const int8_t* wq, const float* bias, co
     return Q8_OK;
 }
 
-// Checks, fills the epilogue and picks the MFMA kernel or the generic one.
-q8_status linear_launch(const int8_t* xq, const int8_t* wq, const float* bias, const float* sx, const float* sw,
-                        int n_groups, int64_t M, int64_t N, int64_t K, void* y, int32_t* acc_out, float* out_amax,
-                        const float* next_scale, const float* residual, uint32_t flags, void* stream)
+q8::Epilogue make_epilogue(const float* bias, const float* sx, const float* sw, int n_groups, int64_t N, void* y,
+                           int32_t* acc_out, float* out_amax, const float* next_scale, const float* residual,
+                           uint32_t flags)
 {
-    q8_status s = check_linear(xq, wq, bias, sx, sw, n_groups, M, N, K, y, acc_out, out_amax, next_scale, flags);
-    if (s != Q8_OK || M == 0 || N == 0) return s;
     q8::Epilogue ep;
     ep.residual = residual;
     ep.bias = bias;
@@ -77,6 +74,17 @@ q8_status linear_launch(const int8_t* xq, const int8_t* wq, const float* bias, c
     ep.out_amax = out_amax;
     ep.next_scale = next_scale;
     ep.flags = flags;
+    return ep;
+}
+
+// Checks, fills the epilogue and picks the MFMA kernel or the generic one.
+q8_status linear_launch(const int8_t* xq, const int8_t* wq, const float* bias, const float* sx, const float* sw,
+                        int n_groups, int64_t M, int64_t N, int64_t K, void* y, int32_t* acc_out, float* out_amax,
+                        const float* next_scale, const float* residual, uint32_t flags, void* stream)
+{
+    q8_status s = check_linear(xq, wq, bias, sx, sw, n_groups, M, N, K, y, acc_out, out_amax, next_scale, flags);
+    if (s != Q8_OK || M == 0 || N == 0) return s;
+    const q8::Epilogue ep = make_epilogue(bias, sx, sw, n_groups, N, y, acc_out, out_amax, next_scale, residual, flags);
     int rc = q8::gemm_mfma_eligible(xq, wq, M, N, K)
                  ? q8::launch_gemm_mfma(xq, wq, M, N, K, ep, as_stream(stream))
                  : q8::launch_gemm_generic(xq, wq, M, N, K, ep, as_stream(stream));
@@ -176,6 +184,12 @@ q8_status q8_linear_f32(const float* x, const int8_t* wq, const float* bias, con
     if (s != Q8_OK) return s;
     if (M > 0 && K > 0 && (!x || !xq_work)) return Q8_ERR_NULL;
     if (misaligned(x, 4)) return Q8_ERR_ALIGN;
+    // a handful of tokens: quantizer and GEMM in one launch (the layer is bound by launch latency there)
+    if (q8::fc_small_eligible(x, wq, M, N, K, flags) && !misaligned(xq_work, 4)) {
+        const q8::Epilogue ep =
+            make_epilogue(bias, scal_work + 1, sw, n_groups, N, y, acc_out, out_amax, next_scale, nullptr, flags);
+        return q8::launch_fc_small(x, wq, M, N, K, xq_work, scal_work, ep, as_stream(stream)) ? Q8_ERR_LAUNCH : Q8_OK;
+    }
     s = q8_quantize_dynamic(x, M * K, xq_work, scal_work, (flags & Q8_EPI_ABSMAX) ? out_amax : nullptr, stream);
     if (s != Q8_OK) return s;
     return q8_linear(xq_work, wq, bias, scal_work + 1, sw, n_groups, M, N, K, y, acc_out, out_amax, next_scale, flags,

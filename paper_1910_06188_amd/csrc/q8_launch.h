@@ -57,6 +57,13 @@ int launch_gemm_mfma(const int8_t* xq, const int8_t* wq, int64_t M, int64_t N, i
 int launch_gemm_generic(const int8_t* xq, const int8_t* wq, int64_t M, int64_t N, int64_t K, const Epilogue& ep,
                         hipStream_t st);
 
+// The dynamic-quantization FC layer of at most 32 tokens in one launch (q8_fc_small.hip): every workgroup runs the
+// quantizer itself and keeps the codes in LDS.  Eligible: M <= 32, M * K <= 16384, K a multiple of 128 up to 1024,
+// 16-byte aligned x and wq, no abs-max epilogue.  scal_out[0] = max|x|, scal_out[1] = S_x, xq_out = the codes.
+bool fc_small_eligible(const float* x, const int8_t* wq, int64_t M, int64_t N, int64_t K, unsigned flags);
+int launch_fc_small(const float* x, const int8_t* wq, int64_t M, int64_t N, int64_t K, int8_t* xq_out, float* scal_out,
+                    const Epilogue& ep, hipStream_t st);
+
 int launch_embedding(const int8_t* table, const float* scale, int64_t V, int64_t H, const int32_t* ids, int64_t T,
                      void* out, int out_is_int8, int32_t* err_flag, hipStream_t st);
 int launch_embedding_sum3(const int8_t* word, int64_t Vw, const int8_t* pos, int64_t Vp, const int8_t* type,

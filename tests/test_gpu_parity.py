@@ -651,6 +651,54 @@ def test_linear_f32_slots_equals_chain(q8):
     assert raw.q8_linear_f32_slots(p, p, 0, p, None, p, 1, 4, 4, 128, p, p, p, None, None, None, 0, None) == 2      # n_slots < 1
 
 
+@pytest.mark.parametrize("M,K,N,groups", [(16, 768, 768, 1), (1, 128, 1, 1), (21, 768, 70, 1), (22, 768, 64, 1), (32, 512, 130, 1),
+                                           (16, 1024, 3072, 3), (17, 1024, 64, 1), (5, 256, 200, 2), (32, 384, 96, 1), (8, 1152, 64, 1)])
+def test_linear_f32_few_tokens_one_launch(q8, M, K, N, groups):
+    """Section 4.1 + Section 3 for a handful of tokens: the one-launch kernel (every workgroup runs the quantizer itself,
+    codes stay in LDS) where it applies, the two-launch path just outside it (M * K > 16384, K > 1024): every
+    intermediate against the oracle, every epilogue, and byte for byte what the chain of separate calls gives."""
+    g = synth.rng(7000 + M + K + N)
+    x = synth.activations(g, M, K)
+    x[int(g.integers(0, M)), int(g.integers(0, K))] = np.float32(-6.25)
+    Ws = [synth.weights(g, N // groups, K) for _ in range(groups)]
+    b = (g.standard_normal(N) * 0.05).astype(np.float32)
+    q = [O.quantize_tensor(Wp) for Wp in Ws]
+    wq_h, sw_h = np.concatenate([a for a, _ in q], 0), np.array([s_ for _, s_ in q], np.float32)
+    ref = O.linear(x, wq_h, sw_h, b, threads=8)
+    ref_g = O.gelu(ref["y"])
+    xd, wq, sw, bd = dev(x), dev(wq_h), dev(sw_h), dev(b)
+    ns_h = np.float32(127.0 / max(float(np.abs(ref_g).max()), 1e-6))
+    ns = scalar(float(ns_h))
+    for flags in (0, q8.EPI_GELU, q8.EPI_REQUANT, q8.EPI_GELU | q8.EPI_REQUANT):
+        xq_work = torch.full((M * K,), 99, dtype=torch.int8, device="cuda")
+        scal = torch.full((q8.SCAL_WORK,), -3.0, device="cuda")
+        y = torch.full((M, N), 77, dtype=torch.int8 if flags & 4 else torch.float32, device="cuda")
+        acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+        q8.q8_linear_f32(xd, wq, bd, sw, xq_work, scal, y, n_groups=groups, acc_out=acc if flags == 0 else None,
+                         next_scale=ns if flags & 4 else None, flags=flags)
+        # the chain of separate calls on the same data
+        a2, s2 = scalar(0.0), scalar(0.0)
+        xq2 = torch.empty((M, K), dtype=torch.int8, device="cuda")
+        y2 = torch.empty_like(y)
+        q8.q8_absmax(xd, a2, s2)
+        q8.q8_quantize(xd, s2, xq2)
+        q8.q8_linear(xq2, wq, bd, s2, sw, y2, n_groups=groups, next_scale=ns if flags & 4 else None, flags=flags)
+        torch.cuda.synchronize()
+        sh = host(scal)
+        assert sh[0] == np.float32(6.25) and sh[1] == ref["sx"]
+        np.testing.assert_array_equal(host(xq_work).reshape(M, K), ref["xq"])
+        np.testing.assert_array_equal(host(y), host(y2))
+        if flags == 0:
+            np.testing.assert_array_equal(host(acc), ref["acc"])
+            assert_rel(host(y), ref["y"])
+        elif flags == q8.EPI_GELU:
+            assert np.all(np.abs(host(y).astype(np.float64) - ref_g) <= 1e-6 + 1e-5 * np.abs(ref_g))
+        elif flags == q8.EPI_REQUANT:
+            yf = torch.empty((M, N), device="cuda")
+            q8.q8_linear(xq2, wq, bd, s2, sw, yf, n_groups=groups)
+            np.testing.assert_array_equal(host(y), O.quantize(host(yf), ns_h))     # codes of the GPU's own fp32 outputs
+
+
 @pytest.mark.parametrize("n", [4096, 16383, 16384, 16385])
 def test_linear_f32_small_tensor_single_launch_boundary(q8, n):
     """Around the size up to which one workgroup does abs-max, scale and quantize in one launch: same bytes on
