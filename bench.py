@@ -529,7 +529,7 @@ def main():
     del xq1, w1c
     # ---- the paper's own inference mode (stored activation scales, Eq. 4), reported beside the headline ---------------------
     layer.calibrate_static()
-    n_static = max(10, args.steps // 4)
+    n_static = max(50, args.steps // 4)   # at least 50: the synchronisation at both ends weighs on shorter runs
     n_warm = max(20, args.warmup // 4)
     dts = timed(torch, layer.step_static, n_static, n_warm)
     out["static_scale_mode"] = {"ms_per_step": round(dts * 1e3, 4), "int8_tops": round(layer.gemm_ops / dts / 1e12, 2),

@@ -94,9 +94,17 @@ def _ptr(t):
     return t.data_ptr()
 
 
+# The current stream's raw handle without building a torch.cuda.Stream object for it (2.7 us per call, about
+# as much as the launch itself); the public accessor is the fallback.
+_raw_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+
+
 def _stream(stream=None):
-    s = torch.cuda.current_stream() if stream is None else stream
-    return s.cuda_stream
+    if stream is not None:
+        return stream.cuda_stream
+    if _raw_stream is not None:
+        return _raw_stream(torch.cuda.current_device())
+    return torch.cuda.current_stream().cuda_stream
 
 
 def version() -> str:
