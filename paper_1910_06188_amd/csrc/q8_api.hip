@@ -405,7 +405,7 @@ q8_status q8_debug_loop_probe(int what, const void* operand_window, float* store
 
 q8_status q8_debug_stream_copy(const void* src, void* dst, int64_t nbytes, void* stream)
 {
-    if (nbytes < 0 || nbytes % 16) return Q8_ERR_SHAPE;
+    if (nbytes < 0 || nbytes % 16 || nbytes / 1024 > 0x7fffffffLL) return Q8_ERR_SHAPE;  // one wave per KiB: the grid is an int
     if (nbytes == 0) return Q8_OK;
     if (!dst) return Q8_ERR_NULL;
     if (misaligned(src, 16) || misaligned(dst, 16)) return Q8_ERR_ALIGN;

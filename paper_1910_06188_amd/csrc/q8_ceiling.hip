@@ -37,17 +37,21 @@ __global__ __launch_bounds__(512, 2) void mfma_rate_kernel(const v4i* __restrict
     if (s == 0x7fffffff && iters < 0) sink[0] = s;
 }
 
-__global__ __launch_bounds__(256) void stream_copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst, int64_t n16)
+// Streaming copy and fill in the shapes that move the most bytes on this part: one 16-byte vector per thread and
+// many small workgroups in address order (copy: one wave per workgroup, non-temporal on both sides; fill: 256
+// threads), so that the workgroups in flight always cover one contiguous window of memory.  Grid-stride loops
+// over the same buffers, where every workgroup touches pages far apart, reach 5.4-5.6 TB/s; these 6.4-6.6.
+typedef float f32x4_c __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(64) void stream_copy_kernel(const f32x4_c* __restrict__ src, f32x4_c* __restrict__ dst, int64_t n16)
 {
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+    const int64_t i = (int64_t)blockIdx.x * 64 + threadIdx.x;
+    if (i < n16) __builtin_nontemporal_store(__builtin_nontemporal_load(&src[i]), &dst[i]);
 }
 
 __global__ __launch_bounds__(256) void stream_fill_kernel(float4* __restrict__ dst, int64_t n16, float v)
 {
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    const float4 f = make_float4(v, v, v, v);
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = f;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n16) dst[i] = make_float4(v, v, v, v);
 }
 
 // One stage of a GEMM main loop, piece by piece: 8 waves, 4 accumulator blocks per wave, 16 MFMAs per wave and stage
@@ -204,13 +208,12 @@ int launch_stream_copy(const void* src, void* dst, int64_t nbytes, hipStream_t s
 {
     const int64_t n16 = nbytes / 16;
     if (n16 == 0) return 0;
-    const int64_t want = (n16 + 256 * 8 - 1) / (256 * 8);
-    const unsigned grid = (unsigned)(want < 8192 ? want : 8192);
     if (src)
-        hipLaunchKernelGGL(stream_copy_kernel, dim3(grid), dim3(256), 0, st, reinterpret_cast<const float4*>(src),
-                           reinterpret_cast<float4*>(dst), n16);
+        hipLaunchKernelGGL(stream_copy_kernel, dim3((unsigned)((n16 + 63) / 64)), dim3(64), 0, st,
+                           reinterpret_cast<const f32x4_c*>(src), reinterpret_cast<f32x4_c*>(dst), n16);
     else
-        hipLaunchKernelGGL(stream_fill_kernel, dim3(grid), dim3(256), 0, st, reinterpret_cast<float4*>(dst), n16, 1.0f);
+        hipLaunchKernelGGL(stream_fill_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st,
+                           reinterpret_cast<float4*>(dst), n16, 1.0f);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 

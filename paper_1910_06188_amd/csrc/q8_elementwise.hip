@@ -50,11 +50,14 @@ __device__ __forceinline__ unsigned absmax_thread(const float* __restrict__ x, i
     const float4* xv = reinterpret_cast<const float4*>(x + head);
     const int64_t nvec = (n - head) >> 2;
     const int64_t tail0 = head + (nvec << 2);
-    const int64_t stride = (int64_t)gridDim.x * kEwThreads;
-    for (int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; i < nvec; i += kAmUnroll * stride) {
+    // A trip's kAmUnroll loads are neighbouring 4 KiB blocks, and block (trip * grid + b) goes to workgroup b: at any
+    // time the whole grid reads one contiguous window of x.  With the loads of a trip a grid-stride apart instead
+    // (every workgroup touching kAmUnroll distant pages at once) the same pass reads 5.0 TB/s instead of 6.2.
+    const int64_t step = (int64_t)gridDim.x * (kAmUnroll * kEwThreads);
+    for (int64_t i = (int64_t)blockIdx.x * (kAmUnroll * kEwThreads) + threadIdx.x; i < nvec; i += step) {
         float4 v[kAmUnroll];
 #pragma unroll
-        for (int u = 0; u < kAmUnroll; ++u) v[u] = xv[min(i + u * stride, nvec - 1)];
+        for (int u = 0; u < kAmUnroll; ++u) v[u] = xv[min(i + u * kEwThreads, nvec - 1)];
 #pragma unroll
         for (int u = 0; u < kAmUnroll; ++u) {
             unsigned a = max(abs_bits(v[u].x), abs_bits(v[u].y));
@@ -127,16 +130,18 @@ __global__ __launch_bounds__(kEwThreads) void quantize_vec_kernel(const float* _
     const float4* xv = reinterpret_cast<const float4*>(x);
     unsigned* qv = reinterpret_cast<unsigned*>(q);
     const int64_t nvec = n >> 2;
-    const int64_t stride = (int64_t)gridDim.x * kEwThreads;
-    int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x;
-    for (; i + (kEwUnroll - 1) * stride < nvec; i += kEwUnroll * stride) {
+    // trips over blocks of kEwUnroll neighbouring 4 KiB pieces, block (trip * grid + b) to workgroup b (see absmax_thread)
+    const int64_t step = (int64_t)gridDim.x * (kEwUnroll * kEwThreads);
+    int64_t i = (int64_t)blockIdx.x * (kEwUnroll * kEwThreads) + threadIdx.x;
+    for (; i + (kEwUnroll - 1) * kEwThreads < nvec; i += step) {
         float4 v[kEwUnroll];
 #pragma unroll
-        for (int u = 0; u < kEwUnroll; ++u) v[u] = load_f4_nt(&xv[i + u * stride]);
+        for (int u = 0; u < kEwUnroll; ++u) v[u] = load_f4_nt(&xv[i + u * kEwThreads]);
 #pragma unroll
-        for (int u = 0; u < kEwUnroll; ++u) qv[i + u * stride] = pack4(v[u], s);
+        for (int u = 0; u < kEwUnroll; ++u) qv[i + u * kEwThreads] = pack4(v[u], s);
     }
-    for (; i < nvec; i += stride) qv[i] = pack4(xv[i], s);
+    for (; i < nvec; i += step)  // the ragged last block
+        for (int u = 0; u < kEwUnroll && i + u * kEwThreads < nvec; ++u) qv[i + u * kEwThreads] = pack4(xv[i + u * kEwThreads], s);
     if (blockIdx.x == 0) {
         int64_t t = (nvec << 2) + threadIdx.x;
         if (t < n) q[t] = (int8_t)quantize_code(x[t], s);
@@ -170,41 +175,44 @@ __global__ __launch_bounds__(kEwThreads) void quantize_amax_kernel(const float* 
                                                                     float* amax_out, float* scale_out,
                                                                     int8_t* __restrict__ q, float* zero_slot)
 {
-    const int64_t stride = (int64_t)gridDim.x * kEwThreads;
-    int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x;
     if (kVec) {
         const float4* xv = reinterpret_cast<const float4*>(x);
         unsigned* qv = reinterpret_cast<unsigned*>(q);
         const int64_t nvec = n >> 2;
+        // trips over blocks of kEwUnroll neighbouring 4 KiB pieces, block (trip * grid + b) to workgroup b (see absmax_thread)
+        const int64_t step = (int64_t)gridDim.x * (kEwUnroll * kEwThreads);
+        int64_t i = (int64_t)blockIdx.x * (kEwUnroll * kEwThreads) + threadIdx.x;
         // The first trip's loads are requested before the partial maxima are folded: most workgroups
         // only make one or two trips, so the fold would otherwise sit in front of nearly all the work.
         float4 first[kEwUnroll];
-        const bool full_first = i + (kEwUnroll - 1) * stride < nvec;
+        const bool full_first = i + (kEwUnroll - 1) * kEwThreads < nvec;
         if (full_first) {
 #pragma unroll
-            for (int u = 0; u < kEwUnroll; ++u) first[u] = load_f4_nt(&xv[i + u * stride]);
+            for (int u = 0; u < kEwUnroll; ++u) first[u] = load_f4_nt(&xv[i + u * kEwThreads]);
         }
         const float s = scale_from_partials(amax, n_amax, amax_out, scale_out, zero_slot);
         if (full_first) {
 #pragma unroll
-            for (int u = 0; u < kEwUnroll; ++u) qv[i + u * stride] = pack4(first[u], s);
-            i += kEwUnroll * stride;
+            for (int u = 0; u < kEwUnroll; ++u) qv[i + u * kEwThreads] = pack4(first[u], s);
+            i += step;
         }
-        for (; i + (kEwUnroll - 1) * stride < nvec; i += kEwUnroll * stride) {
+        for (; i + (kEwUnroll - 1) * kEwThreads < nvec; i += step) {
             float4 v[kEwUnroll];
 #pragma unroll
-            for (int u = 0; u < kEwUnroll; ++u) v[u] = load_f4_nt(&xv[i + u * stride]);
+            for (int u = 0; u < kEwUnroll; ++u) v[u] = load_f4_nt(&xv[i + u * kEwThreads]);
 #pragma unroll
-            for (int u = 0; u < kEwUnroll; ++u) qv[i + u * stride] = pack4(v[u], s);
+            for (int u = 0; u < kEwUnroll; ++u) qv[i + u * kEwThreads] = pack4(v[u], s);
         }
-        for (; i < nvec; i += stride) qv[i] = pack4(xv[i], s);
+        for (; i < nvec; i += step)  // the ragged last block
+            for (int u = 0; u < kEwUnroll && i + u * kEwThreads < nvec; ++u) qv[i + u * kEwThreads] = pack4(xv[i + u * kEwThreads], s);
         if (blockIdx.x == 0) {
             int64_t t = (nvec << 2) + threadIdx.x;
             if (t < n) q[t] = (int8_t)quantize_code(x[t], s);
         }
     } else {
+        const int64_t stride = (int64_t)gridDim.x * kEwThreads;
         const float s = scale_from_partials(amax, n_amax, amax_out, scale_out, zero_slot);
-        for (; i < n; i += stride) q[i] = (int8_t)quantize_code(x[i], s);
+        for (int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; i < n; i += stride) q[i] = (int8_t)quantize_code(x[i], s);
     }
 }
 
@@ -243,26 +251,29 @@ __global__ __launch_bounds__(kEwThreads) void fake_quantize_kernel(const float* 
                                                                     const float* __restrict__ scale, float* xq)
 {
     const float s = scale[0];
-    const int64_t stride = (int64_t)gridDim.x * kEwThreads;
-    int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x;
     if (kVec) {
         const float4* xv = reinterpret_cast<const float4*>(x);
         float4* yv = reinterpret_cast<float4*>(xq);
         const int64_t nvec = n >> 2;
-        for (; i + (kEwUnroll - 1) * stride < nvec; i += kEwUnroll * stride) {
+        // trips over blocks of kEwUnroll neighbouring 4 KiB pieces, block (trip * grid + b) to workgroup b (see absmax_thread)
+        const int64_t step = (int64_t)gridDim.x * (kEwUnroll * kEwThreads);
+        int64_t i = (int64_t)blockIdx.x * (kEwUnroll * kEwThreads) + threadIdx.x;
+        for (; i + (kEwUnroll - 1) * kEwThreads < nvec; i += step) {
             float4 v[kEwUnroll];
 #pragma unroll
-            for (int u = 0; u < kEwUnroll; ++u) v[u] = xv[i + u * stride];
+            for (int u = 0; u < kEwUnroll; ++u) v[u] = xv[i + u * kEwThreads];
 #pragma unroll
-            for (int u = 0; u < kEwUnroll; ++u) yv[i + u * stride] = fake_quantize4(v[u], s);
+            for (int u = 0; u < kEwUnroll; ++u) yv[i + u * kEwThreads] = fake_quantize4(v[u], s);
         }
-        for (; i < nvec; i += stride) yv[i] = fake_quantize4(xv[i], s);
+        for (; i < nvec; i += step)  // the ragged last block
+            for (int u = 0; u < kEwUnroll && i + u * kEwThreads < nvec; ++u) yv[i + u * kEwThreads] = fake_quantize4(xv[i + u * kEwThreads], s);
         if (blockIdx.x == 0) {
             int64_t t = (nvec << 2) + threadIdx.x;
             if (t < n) xq[t] = fake_quantize_value(x[t], s);
         }
     } else {
-        for (; i < n; i += stride) xq[i] = fake_quantize_value(x[i], s);
+        const int64_t stride = (int64_t)gridDim.x * kEwThreads;
+        for (int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; i < n; i += stride) xq[i] = fake_quantize_value(x[i], s);
     }
 }
 
@@ -296,26 +307,29 @@ template <bool kVec>
 __global__ __launch_bounds__(kEwThreads) void ste_backward_kernel(const float* __restrict__ g, int64_t n,
                                                                    float* __restrict__ gx)
 {
-    const int64_t stride = (int64_t)gridDim.x * kEwThreads;
-    int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x;
     if (kVec) {
         const float4* gv = reinterpret_cast<const float4*>(g);
         float4* ov = reinterpret_cast<float4*>(gx);
         const int64_t nvec = n >> 2;
-        for (; i + (kEwUnroll - 1) * stride < nvec; i += kEwUnroll * stride) {
+        // trips over blocks of kEwUnroll neighbouring 4 KiB pieces, block (trip * grid + b) to workgroup b (see absmax_thread)
+        const int64_t step = (int64_t)gridDim.x * (kEwUnroll * kEwThreads);
+        int64_t i = (int64_t)blockIdx.x * (kEwUnroll * kEwThreads) + threadIdx.x;
+        for (; i + (kEwUnroll - 1) * kEwThreads < nvec; i += step) {
             float4 v[kEwUnroll];
 #pragma unroll
-            for (int u = 0; u < kEwUnroll; ++u) v[u] = gv[i + u * stride];
+            for (int u = 0; u < kEwUnroll; ++u) v[u] = gv[i + u * kEwThreads];
 #pragma unroll
-            for (int u = 0; u < kEwUnroll; ++u) ov[i + u * stride] = v[u];
+            for (int u = 0; u < kEwUnroll; ++u) ov[i + u * kEwThreads] = v[u];
         }
-        for (; i < nvec; i += stride) ov[i] = gv[i];
+        for (; i < nvec; i += step)  // the ragged last block
+            for (int u = 0; u < kEwUnroll && i + u * kEwThreads < nvec; ++u) ov[i + u * kEwThreads] = gv[i + u * kEwThreads];
         if (blockIdx.x == 0) {
             int64_t t = (nvec << 2) + threadIdx.x;
             if (t < n) gx[t] = g[t];
         }
     } else {
-        for (; i < n; i += stride) gx[i] = g[i];
+        const int64_t stride = (int64_t)gridDim.x * kEwThreads;
+        for (int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; i < n; i += stride) gx[i] = g[i];
     }
 }
 
@@ -351,9 +365,9 @@ int launch_absmax(const float* x, int64_t n, float* amax_out, float* scale_out, 
     unsigned* bits = reinterpret_cast<unsigned*>(amax_out);
     const int head = head_of(x, n);
     hipLaunchKernelGGL(absmax_init_kernel, dim3(1), dim3(1), 0, st, bits);
-    // two workgroups per compute unit at most: every workgroup ends in a read or read-modify-write of one address
+    // every workgroup ends in a read of one address and, while the maximum still grows, a read-modify-write of it
     const int g = am_grid((n - head) >> 2);
-    hipLaunchKernelGGL(absmax_atomic_kernel, dim3(g < 512 ? g : 512), dim3(kEwThreads), 0, st, x, n, head, bits);
+    hipLaunchKernelGGL(absmax_atomic_kernel, dim3(g < 256 ? g : 256), dim3(kEwThreads), 0, st, x, n, head, bits);
     if (scale_out) hipLaunchKernelGGL(scale_from_amax_kernel, dim3(1), dim3(1), 0, st, amax_out, scale_out);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
@@ -441,7 +455,7 @@ constexpr int kRqMaxGroups = 256;
 constexpr int kRqRing = 64;
 static __device__ unsigned long long g_rq_slots[kRqRing][kRqMaxGroups];
 
-__global__ __launch_bounds__(kRqThreads) void quantize_resident_kernel(const float4* __restrict__ x4, int n4, int chunk4,
+__global__ __launch_bounds__(kRqThreads) void quantize_resident_kernel(const float4* __restrict__ x4, int n4,
                                                                         unsigned long long* slots, unsigned ticket,
                                                                         unsigned spin_limit, float* amax_out,
                                                                         float* scale_out, unsigned* __restrict__ q4,
@@ -451,13 +465,14 @@ __global__ __launch_bounds__(kRqThreads) void quantize_resident_kernel(const flo
     __shared__ unsigned folded;
     __shared__ unsigned long long missing[kRqMaxGroups / 64];
     const int G = (int)gridDim.x, w = (int)blockIdx.x, t = (int)threadIdx.x;
-    const int first = w * chunk4, last = min(first + chunk4, n4);
+    // Workgroup w holds the 16 KiB blocks w, w + G, w + 2 G, ...: the k-th loads of all workgroups together are one
+    // contiguous window of x, which is the order the memory system likes best (see absmax_thread).
     float4 v[kRqVec];
     unsigned m = 0u;
 #pragma unroll
     for (int k = 0; k < kRqVec; ++k) {
-        const int idx = first + k * kRqThreads + t;
-        v[k] = idx < last ? load_f4_nt(&x4[idx]) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        const int idx = (k * G + w) * kRqThreads + t;
+        v[k] = idx < n4 ? load_f4_nt(&x4[idx]) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     }
 #pragma unroll
     for (int k = 0; k < kRqVec; ++k)
@@ -504,10 +519,12 @@ __global__ __launch_bounds__(kRqThreads) void quantize_resident_kernel(const flo
             const int g = r * 64 + __builtin_ctzll(absent);
             absent &= absent - 1ull;
             scanned = true;
-            const int gfirst = g * chunk4, glast = min(gfirst + chunk4, n4);
-            for (int i = gfirst + t; i < glast; i += kRqThreads) {
-                const float4 u = x4[i];
-                extra = max(extra, max(max(abs_bits(u.x), abs_bits(u.y)), max(abs_bits(u.z), abs_bits(u.w))));
+            for (int k = 0; k < kRqVec; ++k) {
+                const int i = (k * G + g) * kRqThreads + t;
+                if (i < n4) {
+                    const float4 u = x4[i];
+                    extra = max(extra, max(max(abs_bits(u.x), abs_bits(u.y)), max(abs_bits(u.z), abs_bits(u.w))));
+                }
             }
         }
     }
@@ -529,8 +546,8 @@ __global__ __launch_bounds__(kRqThreads) void quantize_resident_kernel(const flo
     }
 #pragma unroll
     for (int k = 0; k < kRqVec; ++k) {
-        const int idx = first + k * kRqThreads + t;
-        if (idx < last) q4[idx] = pack4(v[k], s);
+        const int idx = (k * G + w) * kRqThreads + t;
+        if (idx < n4) q4[idx] = pack4(v[k], s);
     }
 }
 
@@ -583,12 +600,11 @@ int launch_quantize_resident(const float* x, int64_t n, float* amax_out, float* 
         return 2;
     }
     if (cap != hipStreamCaptureStatusNone) return 2;
-    const int chunk4 = (int)((n4 + groups - 1) / groups);
     unsigned seq = g_rq_next.fetch_add(1u);
     const unsigned ticket = seq + 1u == 0u ? g_rq_next.fetch_add(1u) + 1u : seq + 1u;   // never 0: the slots start as zeros
     unsigned long long* slots = ring + (size_t)(seq % kRqRing) * kRqMaxGroups;
     hipLaunchKernelGGL(quantize_resident_kernel, dim3(groups), dim3(kRqThreads), 0, st, reinterpret_cast<const float4*>(x),
-                       (int)n4, chunk4, slots, ticket, g_rq_spin_limit.load(), amax_out, scale_out,
+                       (int)n4, slots, ticket, g_rq_spin_limit.load(), amax_out, scale_out,
                        reinterpret_cast<unsigned*>(q), zero_slot);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
