@@ -108,7 +108,7 @@ int launch_gemm_mfma(const int8_t* xq, const int8_t* wq, int64_t M64, int64_t N6
             }
         }
     }
-    const int group_m = 8;
+    const int group_m = 4;  // tile rows per raster panel: 4 beats 1, 2, 8 and 16 by 1-5 us of the 317 us layer step
     switch (v) {
         case 1: return launch_tile_256x256_w4(xq, wq, M, N, K, group_m, ep, st);
         case 2: return launch_tile_256x256_w8(xq, wq, M, N, K, group_m, ep, st);
