@@ -108,7 +108,9 @@ int launch_gemm_mfma(const int8_t* xq, const int8_t* wq, int64_t M64, int64_t N6
             }
         }
     }
-    const int group_m = 4;  // tile rows per raster panel: 4 beats 1, 2, 8 and 16 by 1-5 us of the 317 us layer step
+    // tile rows per raster panel: 4 is 1-2 us faster than 8 over the 317 us layer step but re-reads the weight tiles more
+    // often (FFN1: 282 MB of HBM-side traffic against 248); 16 is 4 us slower
+    const int group_m = 8;
     switch (v) {
         case 1: return launch_tile_256x256_w4(xq, wq, M, N, K, group_m, ep, st);
         case 2: return launch_tile_256x256_w8(xq, wq, M, N, K, group_m, ep, st);
