@@ -5,7 +5,9 @@
  *
  * Conventions shared by all entry points
  *   - Every pointer is a DEVICE pointer owned by the caller unless a comment says
- *     "host".  The library never allocates, frees or keeps a pointer.
+ *     "host".  The library never allocates, frees or keeps a pointer.  (Its own state on a GPU is two
+ *     static device arrays that come with the code object: the scratch of q8_linear_f32_static and
+ *     128 KiB of barrier slots for the one-pass dynamic quantizer.)
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     only enqueue work on it: no host synchronisation, no host read of device data.
  *     Data-dependent scalars (abs-max, scales) therefore live in device memory so
