@@ -95,12 +95,18 @@ int launch_gemm_mfma(const int8_t* xq, const int8_t* wq, int64_t M64, int64_t N6
             // rounds of the launch: a last round that fills at most one workgroup per unit of a paired
             // shape runs unshared and ends early
             const int64_t slots = 256 * c.per_cu, full = tiles / slots, rem = tiles % slots;
-            const double rounds = (double)full + (rem == 0 ? 0.0 : (c.per_cu == 2 && rem <= 256) ? 0.6 : 1.0);
+            // a short reduction whose fp32 epilogue carries the GELU: inside the BERT-Large layer step the paired
+            // 192x128 tile wins it (314 us for the whole dynamic step against 320 with 256x256 and 321 with 128x128);
+            // at BERT-Base size (4096 x 3072 x 768) one three-quarter-full round of 256x256 tiles beats one and a
+            // half rounds of 128x128 by 7 us of the 147 us layer: the epilogue of the half-empty last round of a
+            // paired shape has nothing to hide under, so it is counted as a whole round here
+            const bool gelu_f32_short = K < 2048 && !int8_out && (ep.flags & 1u);
+            const double rounds =
+                (double)full + (rem == 0 ? 0.0 : (c.per_cu == 2 && rem <= 256 && !gelu_f32_short) ? 0.6 : 1.0);
             const double slots_used = ((double)tiles / (double)slots) / rounds;
             double prior = K >= 2048 ? c.prior_long : (int8_out ? c.prior_short_i8 : c.prior_short_f32);
-            // a short reduction whose fp32 epilogue carries the GELU: inside the layer step the paired 192x128 tile
-            // wins it (314 us for the whole dynamic step against 320 with 256x256 and 321 with 128x128)
-            if (K < 2048 && !int8_out && (ep.flags & 1u) && c.variant == 6) prior = 1.05;
+            if (gelu_f32_short && c.variant == 6) prior = 1.05;
+            if (gelu_f32_short && c.variant == 2) prior = 1.04;
             const double score = prior * slots_used * inside;
             if (score > best) {
                 best = score;
