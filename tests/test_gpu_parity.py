@@ -860,6 +860,35 @@ def test_quantize_dynamic_one_pass_on_two_streams(q8):
         np.testing.assert_array_equal(host(qs[i]), q_ref)
 
 
+def test_quantize_dynamic_one_pass_many_launches(q8):
+    """Several hundred one-pass launches back to back, sizes alternating and two streams in flight: every launch's
+    maximum and scale are its own tensor's (a barrier that opened early, or a slot read from another launch, would
+    show as a wrong maximum), and the codes of the last launch of each stream are the oracle's."""
+    sizes = [1_048_576, 12_582_912, 3_145_728, 2_097_152]
+    rng = np.random.default_rng(77)
+    xs = {n: torch.randn(n, device="cuda") for n in sizes}
+    peak = {n: float(xs[n].abs().max()) for n in sizes}
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    qs = [torch.empty(max(sizes), dtype=torch.int8, device="cuda") for _ in range(2)]
+    scal = torch.zeros((2, 300, q8.SCAL_WORK), device="cuda")
+    torch.cuda.synchronize()
+    order = []
+    for it in range(300):
+        n = sizes[int(rng.integers(0, len(sizes)))]
+        sidx = it & 1
+        q8.q8_quantize_dynamic(xs[n], qs[sidx][:n], scal[sidx, it], stream=streams[sidx])
+        order.append((sidx, n))
+    torch.cuda.synchronize()
+    sh = host(scal[:, :, :2])
+    for it, (sidx, n) in enumerate(order):
+        assert sh[sidx, it, 0] == np.float32(peak[n]), (it, n)
+        assert sh[sidx, it, 1] == O.scale(np.float32(peak[n])), (it, n)
+    for sidx in range(2):
+        n = [m for s_, m in order if s_ == sidx][-1]
+        q_ref, _ = O.quantize_tensor(host(xs[n]))
+        np.testing.assert_array_equal(host(qs[sidx][:n]), q_ref)
+
+
 def test_linear_is_deterministic(q8):
     d = synth.fc_layer(48, 600, 512, 700)
     a = run_linear(q8, d["x"], d["W"], d["b"])
