@@ -100,7 +100,29 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_rows_kernel(const float*
     // together and their reductions -- chains of dependent cross-lane exchanges -- interleave, so a wave spends its
     // time waiting for memory once per trip instead of once per row.  Each row's arithmetic is unchanged.
     constexpr int kWaves = kLnThreads / 64;
-    for (int64_t row0 = ((int64_t)blockIdx.x * kWaves + wave) * kRows; row0 < M; row0 += (int64_t)gridDim.x * kWaves * kRows) {
+    const int64_t row_step = (int64_t)gridDim.x * kWaves * kRows;
+    // kSrc 0 and 1: the rows of the NEXT trip are requested as soon as this trip's have arrived, so their flight
+    // covers this trip's reductions, normalisation and stores (a wave otherwise has nothing in flight while it
+    // computes, and with four or five waves per SIMD the pass ran at 5 TB/s where a copy gets 6.5).
+    float4 na[kRows][kVec], nr[kRows][kVec];
+    auto request_rows = [&](int64_t r0) {
+#pragma unroll
+        for (int q = 0; q < kRows; ++q) {
+            const int64_t row = r0 + q;
+            const float4* av = reinterpret_cast<const float4*>(a) + row * nvec;
+            const float4* rv = kSrc == 1 ? reinterpret_cast<const float4*>(r) + row * nvec : nullptr;
+#pragma unroll
+            for (int j = 0; j < kVec; ++j) {
+                const int v = j * 64 + lane;
+                const bool in = row < M && v < nvec;
+                na[q][j] = in ? load_f4_nt_ln(&av[v]) : make_float4(0.f, 0.f, 0.f, 0.f);
+                if (kSrc == 1) nr[q][j] = in ? load_f4_nt_ln(&rv[v]) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+    };
+    const int64_t first_row0 = ((int64_t)blockIdx.x * kWaves + wave) * kRows;
+    if (kSrc != 2 && first_row0 < M) request_rows(first_row0);
+    for (int64_t row0 = first_row0; row0 < M; row0 += row_step) {
         float4 x[kRows][kVec];
         bool live[kRows];
 #pragma unroll
@@ -109,6 +131,14 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_rows_kernel(const float*
             live[q] = row < M;
 #pragma unroll
             for (int j = 0; j < kVec; ++j) x[q][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (kSrc != 2) {   // this trip's rows were requested a trip ago
+#pragma unroll
+                for (int j = 0; j < kVec; ++j)
+                    x[q][j] = kSrc == 1 ? make_float4(__fadd_rn(na[q][j].x, nr[q][j].x), __fadd_rn(na[q][j].y, nr[q][j].y),
+                                                      __fadd_rn(na[q][j].z, nr[q][j].z), __fadd_rn(na[q][j].w, nr[q][j].w))
+                                        : na[q][j];
+                continue;
+            }
             if (!live[q]) continue;
             if (kSrc == 2) {
                 const int64_t ia = es.wid[row], ib = es.pid[row], ic = es.tid[row];
@@ -125,23 +155,9 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_rows_kernel(const float*
                         x[q][j] = make_float4((p.x + t1.x) + t2.x, (p.y + t1.y) + t2.y, (p.z + t1.z) + t2.z, (p.w + t1.w) + t2.w);
                     }
                 }
-            } else {
-                const float4* av = reinterpret_cast<const float4*>(a) + row * nvec;
-                const float4* rv = kSrc == 1 ? reinterpret_cast<const float4*>(r) + row * nvec : nullptr;
-#pragma unroll
-                for (int j = 0; j < kVec; ++j) {
-                    const int v = j * 64 + lane;
-                    if (v < nvec) {
-                        x[q][j] = load_f4_nt_ln(&av[v]);
-                        if (kSrc == 1) {
-                            const float4 t = load_f4_nt_ln(&rv[v]);
-                            x[q][j] = make_float4(__fadd_rn(x[q][j].x, t.x), __fadd_rn(x[q][j].y, t.y), __fadd_rn(x[q][j].z, t.z),
-                                                  __fadd_rn(x[q][j].w, t.w));
-                        }
-                    }
-                }
             }
         }
+        if (kSrc != 2 && row0 + row_step < M) request_rows(row0 + row_step);
         double mean[kRows], rstd[kRows];
 #pragma unroll
         for (int q = 0; q < kRows; ++q) {
@@ -292,7 +308,10 @@ static int ln_grid(int64_t M, int rows_per_wave = 1)
     const int64_t per_wg = (int64_t)(kLnThreads / 64) * rows_per_wave;
     const int64_t need = (M + per_wg - 1) / per_wg;
     if (need <= 1) return 1;
-    const int64_t trips = (need + kLnSlots - 1) / kLnSlots;
+    // at most 1024 workgroups (four per compute unit, all resident at once; fewer than the slots): beyond that a
+    // workgroup makes several trips and fetches the next trip's rows under the arithmetic of the current one
+    const int64_t cap = kLnSlots < 1024 ? kLnSlots : 1024;
+    const int64_t trips = (need + cap - 1) / cap;
     return (int)((need + trips - 1) / trips);
 }
 
