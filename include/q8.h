@@ -385,8 +385,9 @@ void q8_debug_set_quantize_one_pass(int enabled, uint32_t barrier_polls);
  *   v_mfma_i32_32x32x32_i8 on operand fragments read once from `operands` (int8[65536], 16-byte aligned; their bit
  *   pattern decides the clock the chip holds): 2 * 32*32*32 * 8 * iters * 8 * workgroups int8 operations, no
  *   memory traffic.  sink int32[1] is never written in practice.
- * q8_debug_stream_copy: dst[0..nbytes) = src[0..nbytes) with 16-byte accesses (src NULL: dst is filled instead);
- *   nbytes a multiple of 16, pointers 16-byte aligned.
+ * q8_debug_stream_copy: dst[0..nbytes) = src[0..nbytes) (src NULL: dst is filled instead), one 16-byte vector per
+ *   thread and many small workgroups in address order -- the shape that moves the most bytes on this part;
+ *   nbytes a multiple of 16 (at most 2^41), pointers 16-byte aligned.
  */
 q8_status q8_debug_mfma_rate(const int8_t* operands, int iters, int workgroups, int32_t* sink, void* stream);
 q8_status q8_debug_stream_copy(const void* src, void* dst, int64_t nbytes, void* stream);
