@@ -60,7 +60,7 @@ typedef enum {
 /* q8_linear epilogue bits. */
 #define Q8_EPI_GELU 1u     /* y <- gelu(y) = y Phi(y), the erf form (not the tanh form), in fp32 (GELU stays
                               FP32: Section 3).  Evaluated as max(y,0) - |y| Q(|y|) with log2 of the normal upper
-                              tail Q fitted on [0, 6] by a degree-7 polynomial: absolute error <= 5.3e-7, i.e. the
+                              tail Q fitted on [0, 6] by a degree-6 polynomial: absolute error <= 5.2e-7, i.e. the
                               result agrees with the exact function within 1e-6 absolute + 1e-5 relative, not
                               within the 1e-6 relative of the FC output itself. */
 #define Q8_EPI_ABSMAX 2u   /* out_amax[0] <- max(out_amax[0], max|y|) over the fp32 outputs of this call */
