@@ -216,6 +216,65 @@ __global__ __launch_bounds__(kEwThreads) void quantize_amax_kernel(const float* 
     }
 }
 
+// Large tensors with one scale known up front (a stored scale, or a single abs-max): one wave per workgroup and
+// 4 KiB of x per wave.  Every lane turns four vectors 1 KiB apart into four packed dwords (each load instruction
+// of the wave covers 1 KiB contiguous), the wave transposes the 256 dwords through LDS, and each lane stores 16
+// consecutive codes with one 16-byte store: the wave writes its 1 KiB of codes with one instruction instead of four
+// of 256 B.  Workgroups run in address order, so at any moment the chip reads one window of x and writes one window
+// of q.  201 MB in, 50 MB out: 38.4 us (6.55 TB/s, what a streaming copy gets) against 40.5-41.3 us for 4-byte
+// stores in any arrangement of workgroups and trips; 50 MB in: 10.9 against 11.3-11.5 us.
+constexpr int kQwVec = 256;  // float4 per wave
+template <bool kFromAmax>
+__global__ __launch_bounds__(64) void quantize_wave_kernel(const float* __restrict__ x, int64_t n,
+                                                           const float* __restrict__ src, float* amax_out,
+                                                           float* scale_out, int8_t* __restrict__ q, float* zero_slot)
+{
+    __shared__ __attribute__((aligned(16))) unsigned codes[kQwVec];
+    const int lane = threadIdx.x;
+    const float4* xv = reinterpret_cast<const float4*>(x);
+    const int64_t nvec = n >> 2;
+    const int64_t base = (int64_t)blockIdx.x * kQwVec;
+    const bool full = base + kQwVec <= nvec;
+    float4 v[4];
+    if (full) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = load_f4_nt(&xv[base + u * 64 + lane]);
+    }
+    float s;
+    if (kFromAmax) {  // src[0] = the abs-max of the tensor: Eq. 3, and the scalars the GEMM that follows reads
+        const float a = __uint_as_float(abs_bits(src[0]));
+        s = scale_from_amax(a);
+        if (blockIdx.x == 0 && lane == 0) {
+            if (amax_out) amax_out[0] = a;
+            scale_out[0] = s;
+            if (zero_slot) zero_slot[0] = 0.0f;
+        }
+    } else {
+        s = src[0];
+    }
+    if (full) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) codes[u * 64 + lane] = pack4(v[u], s);
+        __syncthreads();  // one wave: orders its LDS writes before the read below
+        const uint4 o = *reinterpret_cast<const uint4*>(&codes[4 * lane]);
+        reinterpret_cast<uint4*>(q + 4 * base)[lane] = o;
+    } else {
+        for (int64_t i = base + lane; i < nvec; i += 64) reinterpret_cast<unsigned*>(q)[i] = pack4(xv[i], s);
+    }
+    if (blockIdx.x == 0) {
+        const int64_t t = (nvec << 2) + lane;
+        if (t < n) q[t] = (int8_t)quantize_code(x[t], s);
+    }
+}
+
+// The wave kernel's shape: enough work to fill the chip, codes 16-byte aligned, a grid that fits 31 bits.
+static bool quantize_wave_shape(const float* x, int64_t n, const int8_t* q)
+{
+    const int64_t nvec = n >> 2;
+    return nvec >= 16384 && (nvec + kQwVec - 1) / kQwVec < ((int64_t)1 << 31) && (reinterpret_cast<uintptr_t>(x) & 15) == 0 &&
+           (reinterpret_cast<uintptr_t>(q) & 15) == 0;
+}
+
 // Any alignment.
 __global__ __launch_bounds__(kEwThreads) void quantize_scalar_kernel(const float* __restrict__ x, int64_t n,
                                                                       const float* __restrict__ scale,
@@ -613,7 +672,11 @@ int launch_quantize_amax(const float* x, int64_t n, const float* amax, int n_ama
                          int8_t* q, float* zero_slot, hipStream_t st)
 {
     bool vec = ((reinterpret_cast<uintptr_t>(x) & 15) == 0) && ((reinterpret_cast<uintptr_t>(q) & 3) == 0);
-    if (vec)
+    // one abs-max value, and no slot to clear that later workgroups still have to read
+    if (n_amax == 1 && zero_slot != amax && quantize_wave_shape(x, n, q))
+        hipLaunchKernelGGL(quantize_wave_kernel<true>, dim3((unsigned)(((n >> 2) + kQwVec - 1) / kQwVec)), dim3(64), 0, st, x, n,
+                           amax, amax_out, scale_out, q, zero_slot);
+    else if (vec)
         hipLaunchKernelGGL(quantize_amax_kernel<true>, dim3(ew_grid(n >> 2)), dim3(kEwThreads), 0, st, x, n, amax,
                            n_amax, amax_out, scale_out, q, zero_slot);
     else
@@ -632,7 +695,10 @@ int launch_quantize(const float* x, int64_t n, const float* scale, int8_t* q, hi
 {
     if (n == 0) return 0;
     bool vec = ((reinterpret_cast<uintptr_t>(x) & 15) == 0) && ((reinterpret_cast<uintptr_t>(q) & 3) == 0);
-    if (vec)
+    if (quantize_wave_shape(x, n, q))
+        hipLaunchKernelGGL(quantize_wave_kernel<false>, dim3((unsigned)(((n >> 2) + kQwVec - 1) / kQwVec)), dim3(64), 0, st, x, n,
+                           scale, nullptr, nullptr, q, nullptr);
+    else if (vec)
         hipLaunchKernelGGL(quantize_vec_kernel, dim3(ew_grid(n >> 2)), dim3(kEwThreads), 0, st, x, n, scale, q);
     else
         hipLaunchKernelGGL(quantize_scalar_kernel, dim3(ew_grid(n)), dim3(kEwThreads), 0, st, x, n, scale, q);

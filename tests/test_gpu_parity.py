@@ -777,6 +777,46 @@ def test_quantize_amax_one_value_and_partials(q8):
     np.testing.assert_array_equal(host(q)[1:14], O.quantize(x[1:14], 1.0))
 
 
+@pytest.mark.parametrize("n", [65_536, 65_540, 66_563, 1_048_576 + 259 * 4 + 3, 6_291_456])
+def test_quantize_large_tensors_sixteen_byte_stores(q8, n):
+    """Tensors of 16384 vectors and more with a single scale take the kernel that stores 16 codes per lane: whole 4 KiB blocks,
+    a ragged last block, a tail of 1-3 elements, a stored scale and a single abs-max value (with the scalars and the
+    cleared slot the GEMM behind it reads), codes only inside q, and the 4-byte-store kernel for a q that is not 16-byte aligned."""
+    g = synth.rng(7100 + n % 101)
+    x = g.standard_normal(n, dtype=np.float32) * np.float32(2.5)
+    a = O.absmax(x)
+    s = O.scale(a)
+    want = O.quantize(x, s)
+    xd = dev(x)
+    for qoff in (0, 4, 16):
+        buf = torch.full((n + 64,), 99, dtype=torch.int8, device="cuda")
+        q = buf[qoff:qoff + n]
+        q8.q8_quantize(xd, scalar(float(s)), q)
+        hb = host(buf)
+        np.testing.assert_array_equal(hb[qoff:qoff + n], want)
+        assert np.all(hb[:qoff] == 99) and np.all(hb[qoff + n:] == 99)
+        buf.fill_(99)
+        scale_out, amax_out = scalar(-1.0), scalar(-1.0)
+        q8.q8_quantize_amax(xd, scalar(float(a)), scale_out, q, amax_out=amax_out)
+        hb = host(buf)
+        assert host(scale_out)[0] == s and host(amax_out)[0] == a
+        np.testing.assert_array_equal(hb[qoff:qoff + n], want)
+        assert np.all(hb[:qoff] == 99) and np.all(hb[qoff + n:] == 99)
+    # the FC layer fed by one abs-max value (the previous layer's fused abs-max): quantizer scalars and the cleared slot
+    if n == 6_291_456:
+        M, K, N = 6144, 1024, 128
+        wq = dev(synth.random_int8(g, (N, K)))
+        scal = torch.full((2,), -1.0, device="cuda")
+        xq_work = torch.full((M * K,), 99, dtype=torch.int8, device="cuda")
+        y = torch.empty((M, N), device="cuda")
+        am = scalar(5.0)
+        q8.q8_linear_f32_slots(xd.view(M, K), scalar(float(a)), wq, None, scalar(900.0), xq_work, scal, y, out_amax=am,
+                               flags=q8.EPI_ABSMAX)
+        assert host(scal)[0] == a and host(scal)[1] == s
+        np.testing.assert_array_equal(host(xq_work), want)
+        assert host(am)[0] == np.abs(host(y)).max()
+
+
 @pytest.mark.parametrize("n", [0, 1, 1000, 16384, 16385, 3_145_731])
 def test_quantize_dynamic_is_absmax_scale_quantize(q8, n):
     """The dynamic quantizer of Section 4.1 in one call: max|x|, S = 127 / max (Eq. 3), codes by Eq. 1, all against the oracle;
